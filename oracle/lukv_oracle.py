@@ -1,0 +1,245 @@
+"""CPU oracle for the LU-KV prefill-time eviction path.  TEST INFRASTRUCTURE ONLY.
+
+A plain, slow, fp64 statement of what the path computes, written from the paper:
+  score    - Eq. 1 (scaled-dot-product softmax) applied to the SnapKV observation
+             window (Sec. 2 "Intra-head Eviction Policies", App. D Table 8: window 32,
+             kernel 7), with the always-kept sink / recent window of App. E;
+  allocate - Sec. 4.2 "Efficient Optimization via Convex Hull Relaxation", Eq. 9-10 and
+             App. A.2: convex surrogate, non-increasing marginal gains, unit-by-unit
+             greedy until B_total is spent (Eq. 8's equality constraint);
+  select   - Sec. 3.2 symbol table, M^pi(k): top-k by the metric, descending, with the
+             fixed deterministic tie rule App. A.1 assumes (lowest index first);
+  compact  - Sec. 3.2 / Eq. 3: the retained index set I_{l,h} as a dense per-head cache.
+
+Only tests, the smoke check and the benchmark's cpu_baseline leg may import this
+module.  It shares no code with the HIP path and never calls it.
+
+Parity pins (tests/test_oracle_*.py): hand-worked softmax/pool and hull/greedy cases,
+closed forms, brute-force definitions, unit-level PAVA, exhaustive and DP search.
+Not pinned by anything: whether these scores and budgets reach the paper's
+LongBench / RULER quality (needs model weights and datasets) - parity unpinned.
+
+Readings of points the paper leaves open are listed next to each function.
+"""
+from __future__ import annotations
+
+import math
+from typing import List, Sequence, Tuple
+
+import numpy as np
+
+
+# ----------------------------------------------------------------------------
+# storage decoding (the oracle's own; nothing here is shared with the GPU path)
+# ----------------------------------------------------------------------------
+
+def decode(x: np.ndarray) -> np.ndarray:
+    """Stored tensor -> float64.  uint16 arrays are bfloat16 bit patterns."""
+    if x.dtype == np.uint16:
+        return (x.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+    return x.astype(np.float64)
+
+
+# ----------------------------------------------------------------------------
+# step 1: observation-window score (Eq. 1; SnapKV metric)
+# ----------------------------------------------------------------------------
+
+def window_attention_sum(q_win: np.ndarray, k: np.ndarray, n_kv_heads: int,
+                         scale: float | None = None) -> np.ndarray:
+    """Unpooled metric: for every KV head, the attention mass each cached position
+    receives from the last w queries, summed over the window and averaged over the
+    G query heads that share the KV head.
+
+    q_win [H_q, w, d], k [H_kv, L, d] (float64).  Returns [H_kv, L] float64.
+
+    Eq. 1: A = softmax_j(q.k_j / sqrt(d_h)) over the keys visible to the query.
+    Readings: window row i sits at position L-w+i and sees keys j <= L-w+i (Eq. 1's
+    j <= k); the sum (not mean) over the window ("accumulated attention scores");
+    mean over the group's query heads, taken before pooling.
+    """
+    H_q, w, d = q_win.shape
+    H_kv, L, _ = k.shape
+    G = H_q // n_kv_heads
+    if scale is None:
+        scale = 1.0 / math.sqrt(d)
+    out = np.zeros((H_kv, L), dtype=np.float64)
+    j = np.arange(L)[None, :]
+    t = (L - w + np.arange(w))[:, None]
+    visible = j <= t                                   # [w, L]
+    for c in range(H_kv):
+        acc = np.zeros(L, dtype=np.float64)
+        for g in range(G):
+            s = scale * (q_win[c * G + g] @ k[c].T)    # [w, L]
+            s = np.where(visible, s, -np.inf)
+            m = s.max(axis=1, keepdims=True)
+            e = np.exp(s - m)
+            p = e / e.sum(axis=1, keepdims=True)
+            acc += p.sum(axis=0)
+        out[c] = acc / G
+    return out
+
+
+def max_pool_1d(r: np.ndarray, kernel: int) -> np.ndarray:
+    """Stride-1 max-pool with the window clipped at both ends:
+    out[j] = max r[max(0, j-h) .. min(n-1, j+h)], h = kernel // 2 (kernel odd)."""
+    n = r.shape[-1]
+    h = kernel // 2
+    pad = np.full(r.shape[:-1] + (h,), -np.inf)
+    padded = np.concatenate([pad, r, pad], axis=-1)
+    out = np.full(r.shape, -np.inf)
+    for t in range(kernel):
+        out = np.maximum(out, padded[..., t:t + n])
+    return out
+
+
+def score(q_win: np.ndarray, k: np.ndarray, n_kv_heads: int, window: int,
+          pool_kernel: int, n_sink: int, scale: float | None = None) -> np.ndarray:
+    """Pooled SnapKV score S [H_kv, L] float32.
+
+    The window sum is pooled over the prefix [0, L-w) only; the result is rounded to
+    float32; then the recent window (j >= L-w) and the first n_sink positions are
+    forced to +inf: they are always kept (App. E) and count against the head's budget.
+    """
+    L = k.shape[1]
+    P = L - window
+    if P < 1:
+        raise ValueError("context must be longer than the observation window")
+    r = window_attention_sum(q_win, k, n_kv_heads, scale)
+    s = np.full(r.shape, np.inf, dtype=np.float32)
+    s[:, :P] = max_pool_1d(r[:, :P], pool_kernel).astype(np.float32)
+    s[:, :min(n_sink, L)] = np.inf
+    return s
+
+
+# ----------------------------------------------------------------------------
+# step 2: global head-level budget allocation (Sec. 4.2, Eq. 8-10, App. A.2)
+# ----------------------------------------------------------------------------
+
+def _slope(knots: Sequence[int], U: Sequence[float], a: int, b: int) -> float:
+    """Canonical gain of one unit on the chord a->b: one fp64 subtract, one fp64 divide."""
+    return float((np.float64(U[b]) - np.float64(U[a])) / np.float64(int(knots[b]) - int(knots[a])))
+
+
+def concave_hull(knots: Sequence[int], U: Sequence[float]) -> List[int]:
+    """Indices of the knots on the upper concave hull of (knots[g], U[g]).
+
+    The profiled utility U(i) = L(0) - L(i) is the retained importance mass; the
+    paper's convex non-increasing surrogate of the loss (PAVA on the marginal
+    decreases) is the least concave majorant of U.  Between grid knots U is taken
+    linear, so the hull of the knots is the hull of the curve.  Collinear knots
+    merge (pop on <=), so hull slopes are strictly decreasing.
+    """
+    st: List[int] = []
+    for g in range(len(knots)):
+        st.append(g)
+        while len(st) >= 3 and _slope(knots, U, st[-3], st[-2]) <= _slope(knots, U, st[-2], st[-1]):
+            del st[-2]
+    return st
+
+
+def marginal_gains(knots: Sequence[int], U: Sequence[float]) -> List[Tuple[int, int, float]]:
+    """Hull segments (n_a, n_b, gain): Eq. 9's g(i) = gain for every unit i in (n_a, n_b]."""
+    st = concave_hull(knots, U)
+    return [(int(knots[a]), int(knots[b]), _slope(knots, U, a, b)) for a, b in zip(st[:-1], st[1:])]
+
+
+def _gain_of_unit(segs: List[Tuple[int, int, float]], u: int) -> float:
+    for lo, hi, g in segs:
+        if lo < u <= hi:
+            return g
+    return -math.inf
+
+
+def allocate(curves: np.ndarray, knots: np.ndarray, b_min: np.ndarray, b_max: np.ndarray,
+             B: int) -> Tuple[np.ndarray, int]:
+    """Greedy allocation on the relaxed curves (App. A.2 "Optimality of greedy allocation").
+
+    curves [NH, Gp] float32, knots [NH, Gp] int (knots[:,0] = 0, strictly increasing),
+    b_min/b_max [NH].  Every head first receives b_min units (minimum retention,
+    App. E); then one unit at a time goes to the head whose next unit has the largest
+    gain, until sum(budgets) = B.  Equal gains: lowest head index first.
+    Returns (budgets int32 [NH], status); status 1 = infeasible (budgets = b_min).
+    """
+    NH = curves.shape[0]
+    segs = [marginal_gains(knots[h], curves[h]) for h in range(NH)]
+    budgets = np.array([int(x) for x in b_min], dtype=np.int64)
+    cap = np.minimum(np.array([int(x) for x in b_max], dtype=np.int64), knots[:, -1].astype(np.int64))
+    R = int(B) - int(budgets.sum())
+    if R < 0 or R > int(np.maximum(cap - budgets, 0).sum()) or np.any(budgets > cap):
+        return budgets.astype(np.int32), 1
+
+    def next_gain(h: int) -> float:
+        return _gain_of_unit(segs[h], int(budgets[h]) + 1) if budgets[h] < cap[h] else -math.inf
+
+    nxt = np.array([next_gain(h) for h in range(NH)], dtype=np.float64)
+    for _ in range(R):
+        h = int(np.argmax(nxt))          # first maximum = lowest head index
+        budgets[h] += 1
+        nxt[h] = next_gain(h)
+    return budgets.astype(np.int32), 0
+
+
+def offsets_of(budgets: np.ndarray) -> np.ndarray:
+    """Row offset of every head in the packed outputs: exclusive prefix sum, int64 [NH+1]."""
+    return np.concatenate([[0], np.cumsum(budgets.astype(np.int64))]).astype(np.int64)
+
+
+# ----------------------------------------------------------------------------
+# step 3: per-head top-k (M^pi(k)) and step 4: compaction
+# ----------------------------------------------------------------------------
+
+def select(s: np.ndarray, k: int) -> np.ndarray:
+    """The k positions of largest score, ties to the lowest index, returned ascending."""
+    order = np.argsort(-s.astype(np.float64), kind="stable")
+    return np.sort(order[:k]).astype(np.int32)
+
+
+def compact(x: np.ndarray, idx: np.ndarray) -> np.ndarray:
+    """Rows idx of x [L, d], bit for bit, in the given order."""
+    return x[idx].copy()
+
+
+# ----------------------------------------------------------------------------
+# whole path
+# ----------------------------------------------------------------------------
+
+def evict(q_win: np.ndarray, k: np.ndarray, v: np.ndarray, cu_seqlens: Sequence[int],
+          n_kv_heads: int, window: int, pool_kernel: int, n_sink: int,
+          curves: np.ndarray, knots: np.ndarray, b_min: np.ndarray, b_max: np.ndarray,
+          B: Sequence[int], layers: Sequence[int] | None = None, scale: float | None = None):
+    """score -> allocate -> select -> compact for packed sequences.
+
+    q_win [NL, H_q, n_seqs*w, d], k, v [NL, H_kv, total_len, d] as stored (bf16 bits or
+    f32); curves/knots [n_seqs, NL*H_kv, Gp]; b_min/b_max [n_seqs, NL*H_kv]; B [n_seqs].
+    Heads are ordered (sequence, layer, kv head).  `layers` restricts scoring/selection to
+    some layers (allocation is always global); other layers get empty outputs.
+
+    Returns dict: budgets [n_seqs*NL*H_kv], offsets [..+1], status [n_seqs],
+    pooled {(s, l): [H_kv, L_s] f32}, kept {(s, l, c): int32 idx}, k_out/v_out {(s,l,c): rows}.
+    """
+    NL, H_q = q_win.shape[0], q_win.shape[1]
+    n_seqs = len(cu_seqlens) - 1
+    budgets, status = [], []
+    for s in range(n_seqs):
+        b, st = allocate(curves[s], knots[s], b_min[s], b_max[s], int(B[s]))
+        budgets.append(b)
+        status.append(st)
+    budgets = np.concatenate(budgets)
+    offsets = offsets_of(budgets)
+    pooled, kept, k_out, v_out = {}, {}, {}, {}
+    use_layers = range(NL) if layers is None else layers
+    for s in range(n_seqs):
+        a, b = int(cu_seqlens[s]), int(cu_seqlens[s + 1])
+        for l in use_layers:
+            q = decode(q_win[l, :, s * window:(s + 1) * window, :])
+            kk = decode(k[l, :, a:b, :])
+            S = score(q, kk, n_kv_heads, window, pool_kernel, n_sink, scale)
+            pooled[(s, l)] = S
+            for c in range(n_kv_heads):
+                hi = (s * NL + l) * n_kv_heads + c
+                idx = select(S[c], int(budgets[hi]))
+                kept[(s, l, c)] = idx
+                k_out[(s, l, c)] = compact(k[l, c, a:b, :], idx)
+                v_out[(s, l, c)] = compact(v[l, c, a:b, :], idx)
+    return {"budgets": budgets, "offsets": offsets, "status": np.array(status, dtype=np.int32),
+            "pooled": pooled, "kept": kept, "k_out": k_out, "v_out": v_out}

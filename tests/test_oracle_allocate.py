@@ -1,0 +1,238 @@
+"""Pins for the oracle's allocation, top-k and compaction steps, CPU only.
+
+Hand-worked hull / greedy case (tests/golden), unit-level PAVA on the marginal
+decreases (the paper's own construction of the surrogate, Sec. 4.2), exhaustive
+search and dynamic programming over integer budgets, and invariants.
+"""
+import itertools
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+from oracle import lukv_oracle as O
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden", "hull_greedy_handworked.txt")
+
+
+def _golden():
+    out = {}
+    for line in open(GOLD):
+        line = line.split("#")[0].strip()
+        if line:
+            key, val = [t.strip() for t in line.split("=")]
+            out[key] = val.split()
+    return out
+
+
+def _curves():
+    g = _golden()
+    U = np.array([[float(Fraction(t)) for t in g["U0"]], [float(Fraction(t)) for t in g["U1"]]],
+                 dtype=np.float32)
+    knots = np.tile(np.arange(5, dtype=np.int32), (2, 1))
+    return g, U, knots
+
+
+def test_handworked_hull_and_gains():
+    g, U, knots = _curves()
+    for h in range(2):
+        assert O.concave_hull(knots[h], U[h]) == [int(t) for t in g["hull%d" % h]]
+        per_unit = [O._gain_of_unit(O.marginal_gains(knots[h], U[h]), u) for u in range(1, 5)]
+        assert per_unit == [float(Fraction(t)) for t in g["gain%d" % h]]
+
+
+def test_handworked_budgets_all_B():
+    g, U, knots = _curves()
+    zero, four = np.zeros(2, np.int32), np.full(2, 4, np.int32)
+    for B, want in enumerate(g["budgets"]):
+        b, st = O.allocate(U, knots, zero, four, B)
+        assert st == 0 and b.tolist() == [int(t) for t in want.split(",")]
+    b, st = O.allocate(U, knots, np.ones(2, np.int32), four, 3)
+    assert st == 0 and b.tolist() == [int(t) for t in g["bmin11_B3"][0].split(",")]
+
+
+def test_infeasible_budgets_flagged():
+    _, U, knots = _curves()
+    zero, four = np.zeros(2, np.int32), np.full(2, 4, np.int32)
+    assert O.allocate(U, knots, zero, four, 9)[1] == 1
+    b, st = O.allocate(U, knots, np.full(2, 3, np.int32), four, 5)
+    assert st == 1 and b.tolist() == [3, 3]
+
+
+# --- unit-level PAVA (textbook pool-adjacent-violators on the marginal decreases) ----------
+
+def _pava_nonincreasing(d):
+    """Isotonic regression of d onto non-increasing sequences, equal weights, exact rationals."""
+    blocks = []  # (sum, count)
+    for x in d:
+        blocks.append((Fraction(x), 1))
+        while len(blocks) >= 2 and blocks[-2][0] / blocks[-2][1] < blocks[-1][0] / blocks[-1][1]:
+            s2, c2 = blocks.pop()
+            s1, c1 = blocks.pop()
+            blocks.append((s1 + s2, c1 + c2))
+    out = []
+    for s, c in blocks:
+        out += [s / c] * c
+    return out
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_pava_equals_hull_slopes(seed):
+    rng = np.random.default_rng(100 + seed)
+    T = int(rng.integers(4, 24))
+    dec = rng.integers(0, 9, size=T)                    # per-token importance, integers
+    U = np.concatenate([[0], np.cumsum(dec)]).astype(np.float32)
+    knots = np.arange(T + 1, dtype=np.int32)
+    want = _pava_nonincreasing([int(x) for x in dec])
+    segs = O.marginal_gains(knots, U)
+    got = [O._gain_of_unit(segs, u) for u in range(1, T + 1)]
+    assert all(w >= 0 for w in want)
+    assert all(a >= b for a, b in zip(want, want[1:]))
+    assert got == pytest.approx([float(w) for w in want], rel=1e-15)
+
+
+# --- exhaustive search / DP --------------------------------------------------------------
+
+def _interp(knots, U, b):
+    return float(np.interp(b, knots.astype(np.float64), U.astype(np.float64)))
+
+
+def _hull_value(knots, U, b):
+    st = O.concave_hull(knots, U)
+    return float(np.interp(b, knots[st].astype(np.float64), U[st].astype(np.float64)))
+
+
+def _dp(value, NH, b_min, b_max, B):
+    """Exact optimum of sum_h value(h, b_h) s.t. sum b_h = B, b_min <= b_h <= b_max."""
+    NEG = -1e300
+    best = [NEG] * (B + 1)
+    best[0] = 0.0
+    for h in range(NH):
+        new = [NEG] * (B + 1)
+        for tot in range(B + 1):
+            if best[tot] == NEG:
+                continue
+            for b in range(int(b_min[h]), int(b_max[h]) + 1):
+                if tot + b > B:
+                    break
+                new[tot + b] = max(new[tot + b], best[tot] + value(h, b))
+        best = new
+    return best[B]
+
+
+def _random_problem(seed, NH, Gp, L):
+    rng = np.random.default_rng(seed)
+    z = rng.standard_normal((NH, Gp))
+    U = np.cumsum(0.5 * z * z, axis=1)
+    U[:, 0] = 0
+    U = (np.round(U * 64) / 64).astype(np.float32)       # dyadic values: sums are exact
+    knots = np.tile(((np.arange(Gp) * L) // (Gp - 1)).astype(np.int32), (NH, 1))
+    b_min = rng.integers(0, 3, size=NH).astype(np.int32)
+    b_max = np.full(NH, L, np.int32) - rng.integers(0, 3, size=NH).astype(np.int32)
+    return U, knots, b_min, b_max
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_greedy_matches_dp_on_relaxed_curves(seed):
+    NH, Gp, L = 4, 6, 15
+    U, knots, b_min, b_max = _random_problem(200 + seed, NH, Gp, L)
+    for B in range(int(b_min.sum()), int(b_max.sum()) + 1, 3):
+        b, st = O.allocate(U, knots, b_min, b_max, B)
+        assert st == 0 and int(b.sum()) == B
+        assert np.all(b >= b_min) and np.all(b <= b_max)
+        relaxed = sum(_hull_value(knots[h], U[h], b[h]) for h in range(NH))
+        dp_relaxed = _dp(lambda h, x: _hull_value(knots[h], U[h], x), NH, b_min, b_max, B)
+        assert relaxed == pytest.approx(dp_relaxed, rel=1e-12, abs=1e-12)
+        raw = sum(_interp(knots[h], U[h], b[h]) for h in range(NH))
+        dp_raw = _dp(lambda h, x: _interp(knots[h], U[h], x), NH, b_min, b_max, B)
+        assert raw <= dp_raw + 1e-12 and dp_raw <= relaxed + 1e-12
+
+
+def test_exhaustive_two_heads_matches_greedy_objective():
+    g, U, knots = _curves()
+    zero, four = np.zeros(2, np.int32), np.full(2, 4, np.int32)
+    for B in range(9):
+        b, _ = O.allocate(U, knots, zero, four, B)
+        got = sum(_hull_value(knots[h], U[h], b[h]) for h in range(2))
+        best = max(_hull_value(knots[0], U[0], x) + _hull_value(knots[1], U[1], B - x)
+                   for x in range(5) if 0 <= B - x <= 4)
+        assert got == pytest.approx(best, rel=1e-14)
+    raw3, dp3, rel3 = [float(Fraction(t)) for t in g["raw_B3"]]
+    b, _ = O.allocate(U, knots, zero, four, 3)
+    assert sum(_interp(knots[h], U[h], b[h]) for h in range(2)) == raw3
+    assert _dp(lambda h, x: _interp(knots[h], U[h], x), 2, zero, four, 3) == dp3
+    assert sum(_hull_value(knots[h], U[h], b[h]) for h in range(2)) == pytest.approx(rel3, rel=1e-14)
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_exhaustive_three_heads(seed):
+    NH, Gp, L = 3, 4, 6
+    U, knots, b_min, b_max = _random_problem(300 + seed, NH, Gp, L)
+    for B in range(int(b_min.sum()), int(b_max.sum()) + 1):
+        b, st = O.allocate(U, knots, b_min, b_max, B)
+        assert st == 0
+        got = sum(_hull_value(knots[h], U[h], b[h]) for h in range(NH))
+        best = max(sum(_hull_value(knots[h], U[h], x[h]) for h in range(NH))
+                   for x in itertools.product(*[range(int(b_min[h]), int(b_max[h]) + 1) for h in range(NH)])
+                   if sum(x) == B)
+        assert got == pytest.approx(best, rel=1e-12, abs=1e-12)
+
+
+# --- invariants -------------------------------------------------------------------------
+
+def test_gains_nonnegative_nonincreasing_and_concave_is_own_hull():
+    U, knots, _, _ = _random_problem(400, 5, 12, 40)
+    for h in range(5):
+        g = [s[2] for s in O.marginal_gains(knots[h], U[h])]
+        assert all(x >= 0 for x in g) and all(a > b for a, b in zip(g, g[1:]))
+    x = np.arange(9)
+    conc = np.sqrt(x).astype(np.float32)
+    assert O.concave_hull(x.astype(np.int32), conc) == list(range(9))
+
+
+def test_power_of_two_scaling_and_uniform_split():
+    U, knots, b_min, b_max = _random_problem(401, 5, 12, 40)
+    b1, _ = O.allocate(U, knots, b_min, b_max, 77)
+    b2, _ = O.allocate(U * np.float32(0.25), knots, b_min, b_max, 77)
+    assert b1.tolist() == b2.tolist()
+    same = np.tile(U[:1], (5, 1))
+    zero, full = np.zeros(5, np.int32), np.full(5, 40, np.int32)
+    for B in (3, 17, 101):
+        b, _ = O.allocate(same, knots, zero, full, B)
+        assert int(b.sum()) == B
+        # identical curves: a tied hull segment is filled head by head, lowest index first
+        assert all(b[i] >= b[i + 1] for i in range(4))
+
+
+def test_offsets_are_prefix_sums():
+    assert O.offsets_of(np.array([3, 0, 5], np.int32)).tolist() == [0, 3, 3, 8]
+
+
+# --- top-k and compaction -----------------------------------------------------------------
+
+@pytest.mark.parametrize("seed", range(5))
+def test_select_brute_force_with_ties(seed):
+    rng = np.random.default_rng(500 + seed)
+    n = 60
+    s = rng.integers(0, 6, size=n).astype(np.float32) / 4       # many exact ties
+    s[rng.integers(0, n, 4)] = np.inf
+    s[rng.integers(0, n, 2)] = -0.0
+    for k in (0, 1, 7, 30, n):
+        got = O.select(s, k)
+        # definition: i is kept iff fewer than k positions beat it
+        # (strictly larger score, or equal score and lower index)
+        want = [i for i in range(n)
+                if sum(1 for j in range(n) if s[j] > s[i] or (s[j] == s[i] and j < i)) < k]
+        assert got.tolist() == want
+        assert got.dtype == np.int32
+
+
+def test_compact_is_bitwise_gather():
+    rng = np.random.default_rng(9)
+    x = rng.integers(0, 65536, size=(20, 8)).astype(np.uint16)
+    idx = np.array([0, 3, 19], np.int32)
+    out = O.compact(x, idx)
+    assert out.dtype == x.dtype and np.array_equal(out, x[[0, 3, 19]])
+    out[0, 0] ^= 1
+    assert x[0, 0] != out[0, 0]
