@@ -1,0 +1,147 @@
+/*
+ * lukv.h - C ABI of the LU-KV prefill-time KV-cache eviction path for AMD MI355X (gfx950).
+ *
+ * The path (paper: "Predicting Future Utility: Global Combinatorial Optimization for
+ * Task-Agnostic KV Cache Eviction"):
+ *   score    observation-window attention metric per KV head           (Eq. 1; SnapKV, App. D)
+ *   allocate global head-level budgets on the convex-hull relaxation    (Sec. 4.2, Eq. 8-10, App. A.2)
+ *   select   per-head top-b_{l,h} positions by the metric               (Sec. 3.2 M^pi(k); Sec. 4.3 "Eviction")
+ *   compact  the retained index sets as a dense per-head cache          (Sec. 3.2, Eq. 3)
+ *
+ * Conventions common to every call
+ *   - "device" pointers are GPU memory owned by the caller (any allocator); "host" pointers are
+ *     ordinary process memory read during the call only.  The library never allocates, frees or
+ *     keeps a pointer.  Its only scratch is the caller's workspace `ws` of at least
+ *     lukv_workspace_bytes() bytes, 256-byte aligned; contents need not be initialised and are
+ *     clobbered.  Two calls that share a workspace must not overlap in time.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only enqueue
+ *     work; they never synchronise the host and never copy to or from the host.
+ *   - Results are deterministic: the same inputs give bitwise the same outputs.
+ *   - Return value: LUKV_OK (0) = enqueued; negative = refused on the host, nothing enqueued
+ *     and no output touched.  Conditions only visible on the device are reported through the
+ *     device `status` words.  No C++ exception crosses the boundary.
+ *   - Head order everywhere: flat head index hi = (seq * n_layers + layer) * n_kv_heads + kv_head.
+ *     Sequences are packed along the token axis; sequence s owns tokens
+ *     [cu_seqlens[s], cu_seqlens[s+1]) and window-query rows [s*window, (s+1)*window).
+ *   - Limits: 1 <= n_seqs <= LUKV_MAX_SEQS; head_dim in {64, 128}; (n_q_heads/n_kv_heads)*window
+ *     <= 512 (<= 256 for f32 with head_dim 128); pool_kernel odd, 1..31; every sequence longer
+ *     than `window` and n_sink <= L - window; at most 2^31-1 packed tokens.
+ */
+#ifndef LUKV_H
+#define LUKV_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define LUKV_OK            0
+#define LUKV_EINVAL       (-1)  /* null pointer, bad dimension, stride or limit */
+#define LUKV_EDTYPE       (-2)  /* unknown dtype / unsupported dtype-head_dim combination */
+#define LUKV_EINFEASIBLE  (-3)  /* host-visible infeasible budget (B < 0) */
+#define LUKV_EWORKSPACE   (-4)  /* workspace missing, misaligned or too small */
+#define LUKV_ELAUNCH      (-5)  /* the HIP runtime refused a launch */
+
+#define LUKV_BF16 0             /* Q, K, V stored as bfloat16 */
+#define LUKV_F32  1             /* Q, K, V stored as float32 */
+
+#define LUKV_MAX_SEQS 64
+
+/* device status bits */
+#define LUKV_ST_INFEASIBLE 1    /* allocation: B outside [sum b_min, sum min(b_max, L)] */
+#define LUKV_ST_CLAMPED    2    /* selection: a budget outside [0, L] was clamped */
+
+typedef struct lukv_config {
+  int32_t n_layers;       /* layers in this call */
+  int32_t n_q_heads;      /* query heads per layer */
+  int32_t n_kv_heads;     /* KV heads per layer; must divide n_q_heads (GQA group G) */
+  int32_t head_dim;       /* d_h */
+  int32_t window;         /* observation window w: the last w queries of each sequence */
+  int32_t pool_kernel;    /* 1-D max-pool width p (odd), stride 1, clipped at both ends */
+  int32_t n_sink;         /* first n_sink positions of a sequence are always kept */
+  int32_t dtype;          /* LUKV_BF16 | LUKV_F32: storage type of q_win, k, v */
+  int32_t n_seqs;         /* packed sequences */
+  const int32_t* cu_seqlens; /* HOST [n_seqs+1], cu_seqlens[0] = 0, increasing */
+  int64_t stride_layer, stride_head, stride_tok;    /* element strides of k and v:
+                             x[layer][kv_head][token][0..d) at layer*sl + head*sh + token*st;
+                             the d elements of a row are contiguous; rows 16-byte aligned */
+  int64_t qstride_layer, qstride_head, qstride_tok; /* element strides of q_win:
+                             q_win[layer][q_head][seq*window + i][0..d) */
+  float softmax_scale;    /* 0 => 1/sqrt(head_dim) (Eq. 1) */
+} lukv_config;
+
+/* Bytes of workspace any call below needs for this configuration (host only, pure).
+ * n_grid = grid points per utility curve (0 if lukv_allocate / lukv_evict are not used). */
+int lukv_workspace_bytes(const lukv_config* cfg, int32_t n_grid, int64_t* bytes);
+
+/* Bytes of workspace a stand-alone lukv_allocate call needs (never more than
+ * lukv_workspace_bytes for a configuration with the same heads and n_grid). */
+int lukv_allocate_workspace_bytes(int32_t n_problems, int32_t n_heads, int32_t n_grid,
+                                  int64_t* bytes);
+
+/* Step 1, Eq. 1 + SnapKV metric (App. D Table 8: window 32, kernel 7).
+ * For every KV head: softmax(q.k/sqrt(d)) of each window query over the keys it can see
+ * (window row i of a length-L sequence sits at position L-w+i and sees keys 0..L-w+i), summed
+ * over the w rows, averaged over the G query heads of the group, max-pooled over the prefix
+ * [0, L-w); positions >= L-w and < n_sink are set to +inf (always kept, App. E).
+ *   q_win  device, dtype, strides qstride_*        k  device, dtype, strides stride_*
+ *   pooled device float32 [n_layers][n_kv_heads][total_tokens], written in full. */
+int lukv_score(const lukv_config* cfg, const void* q_win, const void* k, float* pooled,
+               void* ws, int64_t ws_bytes, void* stream);
+
+/* Step 2, Sec. 4.2 / App. A.2: n_problems independent allocations (one per sequence), each over
+ * n_heads heads.  Per head the utility curve (knots[g], curves[g]) is replaced by its upper
+ * concave hull (the PAVA surrogate of Eq. 9); every head first gets b_min; the remaining
+ * B - sum(b_min) units go to the largest marginal gains over all heads (equal gains: lowest
+ * head, then lowest unit), never beyond min(b_max, last knot).  Gains are compared as
+ * (double(U_b) - double(U_a)) / double(n_b - n_a), IEEE, no fused multiply-add.
+ *   curves  device float32 [n_problems][n_heads][n_grid], finite
+ *   knots   device int32   [n_problems][n_heads][n_grid], knots[..][0] = 0, strictly increasing
+ *   b_min, b_max device int32 [n_problems][n_heads]
+ *   B_total HOST int64 [n_problems]
+ *   budgets device int32 [n_problems*n_heads]      (sum over a problem = B_total when feasible)
+ *   offsets device int64 [n_problems*n_heads + 1]  exclusive prefix sum of budgets
+ *   status  device int32 [n_problems]: 0, or LUKV_ST_INFEASIBLE (then budgets = b_min)
+ * Limits: n_problems <= LUKV_MAX_SEQS, 2 <= n_grid. */
+int lukv_allocate(int32_t n_problems, int32_t n_heads, int32_t n_grid,
+                  const float* curves, const int32_t* knots,
+                  const int32_t* b_min, const int32_t* b_max, const int64_t* B_total,
+                  int32_t* budgets, int64_t* offsets, int32_t* status,
+                  void* ws, int64_t ws_bytes, void* stream);
+
+/* Steps 3+4: per head hi keep the budgets[hi] positions of largest pooled score (ties: lowest
+ * position), and gather their K and V rows.
+ *   pooled   device float32 [n_layers][n_kv_heads][total_tokens] (no NaN)
+ *   budgets  device int32 [n_heads_total], offsets device int64 [n_heads_total+1]
+ *   out_rows rows the three outputs hold (normally offsets[n_heads_total]); a row at or beyond
+ *            it is never written, and LUKV_ST_CLAMPED is raised instead
+ *   kept_idx device int32 [out_rows]: kept_idx[offsets[hi] + r] = r-th kept position (within its
+ *            sequence, ascending)
+ *   k_out, v_out device, dtype, [out_rows][head_dim]: row offsets[hi]+r, contiguous
+ *   status   device int32 [1]: 0 or LUKV_ST_CLAMPED (a budget outside [0, L] was clamped, or rows
+ *            were dropped for lack of room) */
+int lukv_select_compact(const lukv_config* cfg, const float* pooled, const int32_t* budgets,
+                        const int64_t* offsets, const void* k, const void* v, int64_t out_rows,
+                        int32_t* kept_idx, void* k_out, void* v_out, int32_t* status,
+                        void* ws, int64_t ws_bytes, void* stream);
+
+/* The whole path: allocate (one problem per sequence over n_layers*n_kv_heads heads, ordered
+ * (layer, kv_head)) -> score -> select -> compact, enqueued back to back.
+ * Arguments as above; pooled may be NULL (scores then stay in the workspace).  kept_idx, k_out
+ * and v_out hold sum(B_total) rows.
+ *   status device int32 [n_seqs + 1]: [s] allocation status of sequence s, [n_seqs] selection. */
+int lukv_evict(const lukv_config* cfg, const void* q_win, const void* k, const void* v,
+               int32_t n_grid, const float* curves, const int32_t* knots,
+               const int32_t* b_min, const int32_t* b_max, const int64_t* B_total,
+               int32_t* budgets, int64_t* offsets, int32_t* kept_idx,
+               void* k_out, void* v_out, float* pooled, int32_t* status,
+               void* ws, int64_t ws_bytes, void* stream);
+
+/* Static description of a return code. */
+const char* lukv_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LUKV_H */

@@ -1,0 +1,268 @@
+// C ABI of liblukv: argument checks, workspace layout, and the order of launches.
+#include <math.h>
+#include <string.h>
+
+#include "lukv_internal.hpp"
+
+namespace lukv {
+
+static inline int64_t align_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
+static inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int validate_config(const lukv_config* cfg, HostCfg* out) {
+  if (!cfg || !out || !cfg->cu_seqlens) return LUKV_EINVAL;
+  if (cfg->dtype != LUKV_BF16 && cfg->dtype != LUKV_F32) return LUKV_EDTYPE;
+  if (cfg->head_dim != 64 && cfg->head_dim != 128) return LUKV_EDTYPE;
+  if (cfg->n_layers < 1 || cfg->n_q_heads < 1 || cfg->n_kv_heads < 1) return LUKV_EINVAL;
+  if (cfg->n_layers > 65535 || cfg->n_kv_heads > 65535) return LUKV_EINVAL;
+  if (cfg->n_q_heads % cfg->n_kv_heads) return LUKV_EINVAL;
+  if (cfg->window < 1 || cfg->n_sink < 0) return LUKV_EINVAL;
+  if (cfg->pool_kernel < 1 || cfg->pool_kernel > 31 || !(cfg->pool_kernel & 1)) return LUKV_EINVAL;
+  if (cfg->n_seqs < 1 || cfg->n_seqs > LUKV_MAX_SEQS) return LUKV_EINVAL;
+  if (!(cfg->softmax_scale >= 0.f) || isinf(cfg->softmax_scale)) return LUKV_EINVAL;
+  const int esize = cfg->dtype == LUKV_F32 ? 4 : 2;
+  const int64_t strides[6] = {cfg->stride_layer, cfg->stride_head, cfg->stride_tok,
+                              cfg->qstride_layer, cfg->qstride_head, cfg->qstride_tok};
+  for (int i = 0; i < 6; ++i)
+    if (strides[i] < 0 || (strides[i] * esize) % 16) return LUKV_EINVAL;
+  if (cfg->stride_tok < cfg->head_dim || cfg->qstride_tok < cfg->head_dim) return LUKV_EINVAL;
+
+  Geom& g = out->g;
+  memset(out, 0, sizeof(*out));
+  g.n_layers = cfg->n_layers;
+  g.n_q_heads = cfg->n_q_heads;
+  g.n_kv_heads = cfg->n_kv_heads;
+  g.group = cfg->n_q_heads / cfg->n_kv_heads;
+  g.head_dim = cfg->head_dim;
+  g.window = cfg->window;
+  g.pool_kernel = cfg->pool_kernel;
+  g.n_sink = cfg->n_sink;
+  g.f32 = cfg->dtype == LUKV_F32;
+  const int64_t rows = (int64_t)g.group * g.window;
+  const int nbm = (g.f32 && g.head_dim == 128) ? 2 : 4;
+  if (rows > 128 * nbm) return LUKV_EINVAL;
+  g.rows = (int32_t)rows;
+  g.row_blocks = (g.rows + 31) / 32;
+  g.row_groups = g.row_blocks <= nbm ? 1 : (g.row_blocks <= 2 * nbm ? 2 : 4);
+  g.blocks_per_group = (g.row_blocks + g.row_groups - 1) / g.row_groups;
+  g.sl = cfg->stride_layer; g.sh = cfg->stride_head; g.st = cfg->stride_tok;
+  g.qsl = cfg->qstride_layer; g.qsh = cfg->qstride_head; g.qst = cfg->qstride_tok;
+  const float scale = cfg->softmax_scale > 0.f ? cfg->softmax_scale : 1.0f / sqrtf((float)g.head_dim);
+  g.scale_log2e = scale * 1.4426950408889634f;
+  g.inv_group = 1.0f / (float)g.group;
+
+  out->seq.n_seqs = cfg->n_seqs;
+  if (cfg->cu_seqlens[0] != 0) return LUKV_EINVAL;
+  int32_t max_len = 0;
+  for (int s = 0; s < cfg->n_seqs; ++s) {
+    const int64_t a = cfg->cu_seqlens[s], b = cfg->cu_seqlens[s + 1];
+    const int64_t L = b - a;
+    if (L <= g.window || g.n_sink > L - g.window) return LUKV_EINVAL;
+    out->seq.cu[s] = (int32_t)a;
+    out->seq.cu[s + 1] = (int32_t)b;
+    if (L > max_len) max_len = (int32_t)L;
+  }
+  g.total_tokens = out->seq.cu[cfg->n_seqs];
+  out->max_len = max_len;
+  out->n_hi = cfg->n_seqs * g.n_layers * g.n_kv_heads;
+  return LUKV_OK;
+}
+
+SeqTab tiles_for(const SeqTab& seq, int tile, int shrink) {
+  SeqTab t = seq;
+  t.tile0[0] = 0;
+  for (int s = 0; s < seq.n_seqs; ++s) {
+    const int len = seq.cu[s + 1] - seq.cu[s] - shrink;
+    t.tile0[s + 1] = t.tile0[s] + (len + tile - 1) / tile;
+  }
+  return t;
+}
+
+WsLayout make_layout(const HostCfg& hc, int32_t n_grid, bool alloc_only) {
+  WsLayout w;
+  memset(&w, 0, sizeof(w));
+  const Geom& g = hc.g;
+  w.n_hi = hc.n_hi;
+  w.max_chunks = (hc.max_len + kChunkKeys - 1) / kChunkKeys;
+  w.max_slices = (hc.max_len + kSliceElems - 1) / kSliceElems;
+  w.rows_padded = g.row_blocks * 32;
+  int64_t off = 0;
+  auto take = [&](int64_t bytes) { const int64_t o = off; off = align_up(off + bytes, 256); return o; };
+  w.zero_off = off;
+  const int64_t n_sel = alloc_only ? 0 : w.n_hi;
+  w.stats_cnt = take(n_sel * 4);
+  w.sel_cnt = take(n_sel * 4 * 4);
+  w.hist = take(n_sel * kRadixPasses * kHistBins * 4);
+  w.alloc_cnt = take(64 * 4);
+  w.zero_bytes = off - w.zero_off;
+  w.partial = take((int64_t)w.n_hi * w.max_chunks * w.rows_padded * 8);
+  w.rowc = take((int64_t)w.n_hi * w.rows_padded * 4);
+  const int64_t score_bytes = (int64_t)g.n_layers * g.n_kv_heads * g.total_tokens * 4;
+  w.raw = take(score_bytes);
+  w.pooled = take(score_bytes);
+  w.sel_state = take(n_sel * 16);
+  w.slice_cnt = take(n_sel * w.max_slices * 8);
+  const int64_t nseg = (int64_t)hc.n_hi * (n_grid > 0 ? n_grid : 0);
+  w.hull = take(nseg * 4);
+  w.seg_key = take(nseg * 8);
+  w.seg_w = take(nseg * 4);
+  w.total = off;
+  return w;
+}
+
+// Zero the counters and histograms of the workspace, and one caller status word if given
+// (a fill kernel rather than a memset node, so that callers may capture the call in a graph).
+__global__ __launch_bounds__(256) void clear_kernel(uint4* p, int64_t n16, int32_t* word) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n16) p[i] = make_uint4(0, 0, 0, 0);
+  if (i == 0 && word) *word = 0;
+}
+
+int launch_clear(const WsLayout& lay, char* ws, int32_t* word, hipStream_t st) {
+  const int64_t n16 = lay.zero_bytes / 16;
+  const int blocks = (int)((n16 + 255) / 256);
+  hipLaunchKernelGGL(clear_kernel, dim3(blocks), dim3(256), 0, st,
+                     reinterpret_cast<uint4*>(ws + lay.zero_off), n16, word);
+  return check_launch();
+}
+
+static int check_ws(const WsLayout& lay, const void* ws, int64_t ws_bytes) {
+  if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u) || ws_bytes < lay.total) return LUKV_EWORKSPACE;
+  return LUKV_OK;
+}
+
+// Layout for a stand-alone lukv_allocate call (no lukv_config).
+static WsLayout alloc_only_layout(int32_t n_problems, int32_t n_heads, int32_t n_grid) {
+  HostCfg hc;
+  memset(&hc, 0, sizeof(hc));
+  hc.n_hi = n_problems * n_heads;
+  hc.max_len = 0;
+  return make_layout(hc, n_grid, true);
+}
+
+}  // namespace lukv
+
+using namespace lukv;
+
+extern "C" {
+
+int lukv_workspace_bytes(const lukv_config* cfg, int32_t n_grid, int64_t* bytes) {
+  if (!bytes || n_grid < 0) return LUKV_EINVAL;
+  HostCfg hc;
+  const int rc = validate_config(cfg, &hc);
+  if (rc) return rc;
+  *bytes = make_layout(hc, n_grid, false).total;
+  return LUKV_OK;
+}
+
+int lukv_allocate_workspace_bytes(int32_t n_problems, int32_t n_heads, int32_t n_grid,
+                                  int64_t* bytes) {
+  if (!bytes || n_problems < 1 || n_problems > LUKV_MAX_SEQS || n_heads < 1 || n_grid < 2)
+    return LUKV_EINVAL;
+  if ((int64_t)n_problems * n_heads > (1 << 24)) return LUKV_EINVAL;
+  *bytes = alloc_only_layout(n_problems, n_heads, n_grid).total;
+  return LUKV_OK;
+}
+
+int lukv_score(const lukv_config* cfg, const void* q_win, const void* k, float* pooled,
+               void* ws, int64_t ws_bytes, void* stream) {
+  HostCfg hc;
+  int rc = validate_config(cfg, &hc);
+  if (rc) return rc;
+  if (!q_win || !k || !pooled || !aligned16(q_win) || !aligned16(k)) return LUKV_EINVAL;
+  const WsLayout lay = make_layout(hc, 0, false);
+  if ((rc = check_ws(lay, ws, ws_bytes))) return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if ((rc = launch_clear(lay, (char*)ws, nullptr, st))) return rc;
+  return launch_score(hc, lay, q_win, k, pooled, (char*)ws, st);
+}
+
+int lukv_allocate(int32_t n_problems, int32_t n_heads, int32_t n_grid, const float* curves,
+                  const int32_t* knots, const int32_t* b_min, const int32_t* b_max,
+                  const int64_t* B_total, int32_t* budgets, int64_t* offsets, int32_t* status,
+                  void* ws, int64_t ws_bytes, void* stream) {
+  if (n_problems < 1 || n_problems > LUKV_MAX_SEQS || n_heads < 1 || n_grid < 2) return LUKV_EINVAL;
+  if ((int64_t)n_problems * n_heads > (1 << 24)) return LUKV_EINVAL;
+  if (!curves || !knots || !b_min || !b_max || !B_total || !budgets || !offsets || !status)
+    return LUKV_EINVAL;
+  for (int i = 0; i < n_problems; ++i)
+    if (B_total[i] < 0) return LUKV_EINFEASIBLE;
+  // the allocation scratch sits at the same offsets as in a full configuration with the
+  // same number of heads only when there is no score/select scratch before it, so a
+  // stand-alone call lays the workspace out on its own
+  const WsLayout lay = alloc_only_layout(n_problems, n_heads, n_grid);
+  int rc;
+  if ((rc = check_ws(lay, ws, ws_bytes))) return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if ((rc = launch_clear(lay, (char*)ws, nullptr, st))) return rc;
+  return launch_allocate(n_problems, n_heads, n_grid, curves, knots, b_min, b_max, B_total, budgets,
+                         offsets, status, lay, (char*)ws, st);
+}
+
+int lukv_select_compact(const lukv_config* cfg, const float* pooled, const int32_t* budgets,
+                        const int64_t* offsets, const void* k, const void* v, int64_t out_rows,
+                        int32_t* kept_idx, void* k_out, void* v_out, int32_t* status, void* ws,
+                        int64_t ws_bytes, void* stream) {
+  HostCfg hc;
+  int rc = validate_config(cfg, &hc);
+  if (rc) return rc;
+  if (!pooled || !budgets || !offsets || !k || !v || !kept_idx || !k_out || !v_out || !status)
+    return LUKV_EINVAL;
+  if (out_rows < 0) return LUKV_EINVAL;
+  if (!aligned16(k) || !aligned16(v) || !aligned16(k_out) || !aligned16(v_out)) return LUKV_EINVAL;
+  const WsLayout lay = make_layout(hc, 0, false);
+  if ((rc = check_ws(lay, ws, ws_bytes))) return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if ((rc = launch_clear(lay, (char*)ws, status, st))) return rc;
+  return launch_select_compact(hc, lay, pooled, budgets, offsets, k, v, kept_idx, k_out, v_out,
+                               out_rows, status, (char*)ws, st);
+}
+
+int lukv_evict(const lukv_config* cfg, const void* q_win, const void* k, const void* v,
+               int32_t n_grid, const float* curves, const int32_t* knots, const int32_t* b_min,
+               const int32_t* b_max, const int64_t* B_total, int32_t* budgets, int64_t* offsets,
+               int32_t* kept_idx, void* k_out, void* v_out, float* pooled, int32_t* status,
+               void* ws, int64_t ws_bytes, void* stream) {
+  HostCfg hc;
+  int rc = validate_config(cfg, &hc);
+  if (rc) return rc;
+  if (n_grid < 2) return LUKV_EINVAL;
+  if (!q_win || !k || !v || !curves || !knots || !b_min || !b_max || !B_total || !budgets ||
+      !offsets || !kept_idx || !k_out || !v_out || !status)
+    return LUKV_EINVAL;
+  if (!aligned16(q_win) || !aligned16(k) || !aligned16(v) || !aligned16(k_out) || !aligned16(v_out))
+    return LUKV_EINVAL;
+  int64_t out_rows = 0;
+  for (int i = 0; i < cfg->n_seqs; ++i) {
+    if (B_total[i] < 0) return LUKV_EINFEASIBLE;
+    out_rows += B_total[i];
+  }
+  const WsLayout lay = make_layout(hc, n_grid, false);
+  if ((rc = check_ws(lay, ws, ws_bytes))) return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  char* w = (char*)ws;
+  float* scores = pooled ? pooled : reinterpret_cast<float*>(w + lay.pooled);
+  int32_t* sel_status = status + cfg->n_seqs;
+  if ((rc = launch_clear(lay, w, sel_status, st))) return rc;
+  const int n_heads = hc.g.n_layers * hc.g.n_kv_heads;
+  if ((rc = launch_allocate(cfg->n_seqs, n_heads, n_grid, curves, knots, b_min, b_max, B_total,
+                            budgets, offsets, status, lay, w, st)))
+    return rc;
+  if ((rc = launch_score(hc, lay, q_win, k, scores, w, st))) return rc;
+  return launch_select_compact(hc, lay, scores, budgets, offsets, k, v, kept_idx, k_out, v_out,
+                               out_rows, sel_status, w, st);
+}
+
+const char* lukv_strerror(int code) {
+  switch (code) {
+    case LUKV_OK: return "ok";
+    case LUKV_EINVAL: return "invalid argument (null pointer, dimension, stride, alignment or limit)";
+    case LUKV_EDTYPE: return "unsupported dtype or head_dim";
+    case LUKV_EINFEASIBLE: return "infeasible budget";
+    case LUKV_EWORKSPACE: return "workspace missing, misaligned or too small";
+    case LUKV_ELAUNCH: return "HIP launch failed";
+    default: return "unknown lukv error code";
+  }
+}
+
+}  // extern "C"

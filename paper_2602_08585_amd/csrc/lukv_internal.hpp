@@ -1,0 +1,97 @@
+// Internal declarations shared by the translation units of liblukv (HIP, gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "lukv.h"
+
+namespace lukv {
+
+// ---- tiling constants -------------------------------------------------------------------
+constexpr int kChunkKeys = 512;    // keys one workgroup of the score kernels streams
+constexpr int kSliceElems = 1024;  // scores one workgroup of the selection kernels owns
+constexpr int kHistBins = 2048;    // bins of one radix pass
+constexpr int kRadixPasses = 3;    // digits of 11, 11 and 10 bits, most significant first
+constexpr int kMaxRows = 512;      // G * window upper bound
+
+// Packed-sequence table passed to kernels by value: sequence boundaries plus the first tile
+// of every sequence for the tile size of the launch.
+struct SeqTab {
+  int32_t n_seqs;
+  int32_t cu[LUKV_MAX_SEQS + 1];     // token offsets
+  int32_t tile0[LUKV_MAX_SEQS + 1];  // tile offsets (prefix sum of tiles per sequence)
+};
+
+// Geometry of a call, by value to every kernel.
+struct Geom {
+  int32_t n_layers, n_q_heads, n_kv_heads, group, head_dim;
+  int32_t window, pool_kernel, n_sink, f32;
+  int32_t rows;        // G * window
+  int32_t row_blocks;  // ceil(rows / 32)
+  int32_t row_groups;  // 1, 2 or 4 wave groups share the row blocks
+  int32_t blocks_per_group;
+  int32_t total_tokens;
+  int64_t sl, sh, st;     // K/V strides (elements)
+  int64_t qsl, qsh, qst;  // Q strides (elements)
+  float scale_log2e;      // softmax scale * log2(e)
+  float inv_group;        // 1 / G
+};
+
+// Byte offsets into the caller's workspace.
+struct WsLayout {
+  int64_t zero_off, zero_bytes;  // region cleared at the start of every call
+  int64_t stats_cnt;             // u32 [n_hi]
+  int64_t sel_cnt;               // u32 [n_hi * 4]
+  int64_t hist;                  // u32 [n_hi * 3 * kHistBins]
+  int64_t alloc_cnt;             // u32 [64]
+  int64_t partial;               // float2 [n_hi * max_chunks * rows_padded]
+  int64_t rowc;                  // float [n_hi * rows_padded]
+  int64_t raw;                   // float [n_layers * n_kv_heads * total_tokens]
+  int64_t pooled;                // float, same shape
+  int64_t sel_state;             // uint4 [n_hi]
+  int64_t slice_cnt;             // uint2 [n_hi * max_slices]
+  int64_t hull;                  // i32 [n_problems * n_heads * n_grid]
+  int64_t seg_key;               // u64 [n_problems * n_heads * n_grid]
+  int64_t seg_w;                 // u32 [n_problems * n_heads * n_grid]
+  int64_t total;
+  int32_t n_hi, max_chunks, max_slices, rows_padded;
+};
+
+struct HostCfg {
+  Geom g;
+  SeqTab seq;       // cu filled, tile0 unset
+  int32_t max_len;  // longest sequence
+  int32_t n_hi;
+};
+
+int validate_config(const lukv_config* cfg, HostCfg* out);
+WsLayout make_layout(const HostCfg& hc, int32_t n_grid, bool alloc_only);
+SeqTab tiles_for(const SeqTab& seq, int tile, int shrink);  // tiles over (L_s - shrink) tokens
+
+// Launchers (enqueue only; return a LUKV_* code).
+int launch_clear(const WsLayout& lay, char* ws, int32_t* word, hipStream_t st);
+int launch_score(const HostCfg& hc, const WsLayout& lay, const void* q, const void* k,
+                 float* pooled_out, char* ws, hipStream_t st);
+int launch_select_compact(const HostCfg& hc, const WsLayout& lay, const float* pooled,
+                          const int32_t* budgets, const int64_t* offsets, const void* k,
+                          const void* v, int32_t* kept_idx, void* k_out, void* v_out,
+                          int64_t out_rows, int32_t* status, char* ws, hipStream_t st);
+int launch_allocate(int32_t n_problems, int32_t n_heads, int32_t n_grid, const float* curves,
+                    const int32_t* knots, const int32_t* b_min, const int32_t* b_max,
+                    const int64_t* B_total, int32_t* budgets, int64_t* offsets, int32_t* status,
+                    const WsLayout& lay, char* ws, hipStream_t st);
+
+inline int check_launch() {
+  return hipGetLastError() == hipSuccess ? LUKV_OK : LUKV_ELAUNCH;
+}
+
+// Sequence / tile lookup for a flat tile index (linear scan, n_seqs <= 64, wave-uniform).
+__device__ inline void find_tile(const SeqTab& tab, int tile, int& seq, int& local_tile) {
+  int s = 0;
+  while (s + 1 < tab.n_seqs && tile >= tab.tile0[s + 1]) ++s;
+  seq = s;
+  local_tile = tile - tab.tile0[s];
+}
+
+}  // namespace lukv

@@ -1,0 +1,85 @@
+"""Host-only checks of the C-ABI library: it loads without a GPU, exports every function
+include/lukv.h declares, and refuses bad configurations on the host (no compute calls)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2602_08585_amd import lukv, synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "lukv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(lukv_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = lukv.load_library()
+    names = _declared()
+    assert set(names) == set(lukv.EXPORTS)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_strerror_covers_codes():
+    for code in (0, -1, -2, -3, -4, -5):
+        assert "unknown" not in lukv.strerror(code)
+    assert "unknown" in lukv.strerror(-99)
+
+
+def _cfg(**kw):
+    base = dict(n_layers=1, n_q_heads=32, n_kv_heads=8, head_dim=128, window=32, pool_kernel=7,
+                n_sink=4, dtype=lukv.LUKV_BF16, cu_seqlens=[0, 32768], stride_layer=8 * 32768 * 128,
+                stride_head=32768 * 128, stride_tok=128, qstride_layer=32 * 32 * 128,
+                qstride_head=32 * 128, qstride_tok=128)
+    base.update(kw)
+    return lukv.Config(**base)
+
+
+def test_workspace_bytes_is_pure_and_monotone():
+    a = lukv.lukv_workspace_bytes(_cfg(), 64)
+    assert a == lukv.lukv_workspace_bytes(_cfg(), 64) and a > 2 * 8 * 32768 * 4
+    assert lukv.lukv_workspace_bytes(_cfg(cu_seqlens=[0, 65536]), 64) > a
+    assert lukv.lukv_allocate_workspace_bytes(1, 8, 64) <= a
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(n_kv_heads=5), lukv.LUKV_EINVAL),             # G not integral
+    (dict(head_dim=96), lukv.LUKV_EDTYPE),
+    (dict(dtype=7), lukv.LUKV_EDTYPE),
+    (dict(pool_kernel=4), lukv.LUKV_EINVAL),            # even kernel
+    (dict(cu_seqlens=[0, 32]), lukv.LUKV_EINVAL),       # context not longer than the window
+    (dict(cu_seqlens=[0, 34]), lukv.LUKV_EINVAL),       # n_sink > L - w
+    (dict(cu_seqlens=[1, 4096]), lukv.LUKV_EINVAL),
+    (dict(stride_tok=100), lukv.LUKV_EINVAL),           # rows not 16-byte aligned / < head_dim
+    (dict(window=256), lukv.LUKV_EINVAL),               # G*w > 512
+    (dict(cu_seqlens=list(range(0, 66 * 64, 64))), lukv.LUKV_EINVAL),   # > LUKV_MAX_SEQS
+    (dict(softmax_scale=-1.0), lukv.LUKV_EINVAL),
+])
+def test_bad_configurations_are_refused(kw, code):
+    with pytest.raises(lukv.LukvError) as e:
+        lukv.lukv_workspace_bytes(_cfg(**kw), 64)
+    assert e.value.code == code
+
+
+def test_named_workloads_are_accepted():
+    for name in ("tiny", "8b_32k", "8b_full_20", "long_128k", "batched"):
+        wl = synth.workload(name)
+        T, d = wl.total_len, wl.head_dim
+        cfg = lukv.Config(wl.n_layers, wl.n_q_heads, wl.n_kv_heads, d, wl.window, wl.pool_kernel,
+                          wl.n_sink, lukv.LUKV_F32 if wl.dtype == synth.F32 else lukv.LUKV_BF16,
+                          wl.cu_seqlens.tolist(), wl.n_kv_heads * T * d, T * d, d,
+                          wl.n_q_heads * wl.n_seqs * wl.window * d, wl.n_seqs * wl.window * d, d)
+        assert lukv.lukv_workspace_bytes(cfg, wl.n_grid) > 0
+
+
+def test_synth_budgets_match_named_configs():
+    assert synth.workload("tiny").budget_total(0) == 819
+    assert synth.workload("8b_32k").budget_total(0) == 52428
+    assert synth.workload("8b_full_20").budget_total(0) == 1677721
+    assert synth.workload("8b_full_10").budget_total(0) == 838860
+    assert synth.workload("long_128k").budget_total(0) == 1677721
