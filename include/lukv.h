@@ -138,6 +138,18 @@ int lukv_evict(const lukv_config* cfg, const void* q_win, const void* k, const v
                void* k_out, void* v_out, float* pooled, int32_t* status,
                void* ws, int64_t ws_bytes, void* stream);
 
+/* Instrumentation for benchmarks (process-wide, not thread-safe; for callers that time the path,
+ * not part of the method).  While n_events > 0, every call records events[i] (hipEvent_t, created
+ * by the caller, passed as void*) on its stream immediately before stage i, and lukv_evict records
+ * events[LUKV_STAGE_END] after its last stage; entries that are NULL or beyond n_events are
+ * skipped.  The array must stay valid until lukv_set_stage_events(NULL, 0).  Stage order:
+ * clear, allocate, score_stats, score_accum, pool, sel_hist0, sel_hist1, sel_hist2, sel_count,
+ * sel_emit, end (lukv_stage_name gives the same names; "" when out of range). */
+#define LUKV_STAGE_END 10
+#define LUKV_NUM_STAGE_EVENTS 11
+int lukv_set_stage_events(void* const* events, int32_t n_events);
+const char* lukv_stage_name(int32_t stage);
+
 /* Static description of a return code. */
 const char* lukv_strerror(int code);
 

@@ -196,6 +196,7 @@ int launch_allocate(int32_t n_problems, int32_t n_heads, int32_t n_grid, const f
   aa.n_heads = n_heads;
   aa.n_grid = n_grid;
   for (int i = 0; i < LUKV_MAX_SEQS; ++i) aa.B[i] = i < n_problems ? B_total[i] : 0;
+  stage_mark(kStAllocate, st);
   hipLaunchKernelGGL(allocate_kernel, dim3(n_problems), dim3(256), 0, st, aa, curves, knots, b_min,
                      b_max, budgets, offsets, status, reinterpret_cast<int32_t*>(ws + lay.hull),
                      reinterpret_cast<unsigned long long*>(ws + lay.seg_key),

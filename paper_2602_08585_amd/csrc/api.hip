@@ -121,9 +121,18 @@ __global__ __launch_bounds__(256) void clear_kernel(uint4* p, int64_t n16, int32
 int launch_clear(const WsLayout& lay, char* ws, int32_t* word, hipStream_t st) {
   const int64_t n16 = lay.zero_bytes / 16;
   const int blocks = (int)((n16 + 255) / 256);
+  stage_mark(kStClear, st);
   hipLaunchKernelGGL(clear_kernel, dim3(blocks), dim3(256), 0, st,
                      reinterpret_cast<uint4*>(ws + lay.zero_off), n16, word);
   return check_launch();
+}
+
+static void* const* g_stage_events = nullptr;
+static int g_n_stage_events = 0;
+
+void stage_mark(int stage, hipStream_t st) {
+  if (g_stage_events && stage < g_n_stage_events && g_stage_events[stage])
+    (void)hipEventRecord(static_cast<hipEvent_t>(g_stage_events[stage]), st);
 }
 
 static int check_ws(const WsLayout& lay, const void* ws, int64_t ws_bytes) {
@@ -249,8 +258,24 @@ int lukv_evict(const lukv_config* cfg, const void* q_win, const void* k, const v
                             budgets, offsets, status, lay, w, st)))
     return rc;
   if ((rc = launch_score(hc, lay, q_win, k, scores, w, st))) return rc;
-  return launch_select_compact(hc, lay, scores, budgets, offsets, k, v, kept_idx, k_out, v_out,
-                               out_rows, sel_status, w, st);
+  rc = launch_select_compact(hc, lay, scores, budgets, offsets, k, v, kept_idx, k_out, v_out,
+                             out_rows, sel_status, w, st);
+  stage_mark(kStEnd, st);
+  return rc;
+}
+
+int lukv_set_stage_events(void* const* events, int32_t n_events) {
+  if (n_events < 0 || (n_events > 0 && !events)) return LUKV_EINVAL;
+  g_stage_events = n_events ? events : nullptr;
+  g_n_stage_events = n_events;
+  return LUKV_OK;
+}
+
+const char* lukv_stage_name(int32_t stage) {
+  static const char* const names[kNumStageEvents] = {
+      "clear", "allocate", "score_stats", "score_accum", "pool", "sel_hist0", "sel_hist1",
+      "sel_hist2", "sel_count", "sel_emit", "end"};
+  return stage >= 0 && stage < kNumStageEvents ? names[stage] : "";
 }
 
 const char* lukv_strerror(int code) {

@@ -82,6 +82,11 @@ int launch_allocate(int32_t n_problems, int32_t n_heads, int32_t n_grid, const f
                     const int64_t* B_total, int32_t* budgets, int64_t* offsets, int32_t* status,
                     const WsLayout& lay, char* ws, hipStream_t st);
 
+// Optional instrumentation (lukv_set_stage_events): record the caller's event for a stage.
+enum Stage { kStClear = 0, kStAllocate, kStStats, kStAccum, kStPool, kStHist0, kStHist1, kStHist2,
+             kStCount, kStEmit, kStEnd, kNumStageEvents };
+void stage_mark(int stage, hipStream_t st);
+
 inline int check_launch() {
   return hipGetLastError() == hipSuccess ? LUKV_OK : LUKV_ELAUNCH;
 }

@@ -318,11 +318,14 @@ static int launch_score_t(const HostCfg& hc, const WsLayout& lay, const void* q,
   dim3 gridA(tabA.tile0[tabA.n_seqs], g.n_kv_heads, g.n_layers);
   dim3 gridB(tabB.tile0[tabB.n_seqs], g.n_kv_heads, g.n_layers);
   dim3 gridP(tabP.tile0[tabP.n_seqs], g.n_kv_heads * g.n_layers, 1);
+  stage_mark(kStStats, st);
   hipLaunchKernelGGL((score_stats_kernel<F32, D, NBM>), gridA, dim3(256), 0, st, g, tabA,
                      (const char*)q, (const char*)k, partial, rowc, cnt, lay.max_chunks,
                      lay.rows_padded);
+  stage_mark(kStAccum, st);
   hipLaunchKernelGGL((score_accum_kernel<F32, D, NBM>), gridB, dim3(256), 0, st, g, tabB,
                      (const char*)q, (const char*)k, (const float*)rowc, raw, lay.rows_padded);
+  stage_mark(kStPool, st);
   hipLaunchKernelGGL(pool_kernel, gridP, dim3(256), 0, st, g, tabP, (const float*)raw, pooled_out);
   return check_launch();
 }

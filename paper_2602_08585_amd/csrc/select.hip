@@ -279,10 +279,15 @@ int launch_select_compact(const HostCfg& hc, const WsLayout& lay, const float* p
   uint4* state = reinterpret_cast<uint4*>(ws + lay.sel_state);
   uint2* slice_cnt = reinterpret_cast<uint2*>(ws + lay.slice_cnt);
   dim3 grid(tab.tile0[tab.n_seqs], g.n_kv_heads, g.n_layers);
+  stage_mark(kStHist0, st);
   hipLaunchKernelGGL(sel_hist_kernel<0>, grid, dim3(256), 0, st, sg, tab, pooled, budgets, hist, cnt, state, status);
+  stage_mark(kStHist1, st);
   hipLaunchKernelGGL(sel_hist_kernel<1>, grid, dim3(256), 0, st, sg, tab, pooled, budgets, hist, cnt, state, status);
+  stage_mark(kStHist2, st);
   hipLaunchKernelGGL(sel_hist_kernel<2>, grid, dim3(256), 0, st, sg, tab, pooled, budgets, hist, cnt, state, status);
+  stage_mark(kStCount, st);
   hipLaunchKernelGGL(sel_count_kernel, grid, dim3(256), 0, st, sg, tab, pooled, (const uint4*)state, slice_cnt);
+  stage_mark(kStEmit, st);
   const int esize = g.f32 ? 4 : 2;
   const int row_bytes = g.head_dim * esize;
   if (row_bytes == 128)

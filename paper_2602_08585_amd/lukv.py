@@ -32,7 +32,10 @@ LUKV_ST_INFEASIBLE = 1
 LUKV_ST_CLAMPED = 2
 
 EXPORTS = ("lukv_workspace_bytes", "lukv_allocate_workspace_bytes", "lukv_score", "lukv_allocate",
-           "lukv_select_compact", "lukv_evict", "lukv_strerror")
+           "lukv_select_compact", "lukv_evict", "lukv_set_stage_events", "lukv_stage_name",
+           "lukv_strerror")
+LUKV_STAGE_END = 10
+LUKV_NUM_STAGE_EVENTS = 11
 
 
 class _CConfig(ctypes.Structure):
@@ -74,8 +77,12 @@ def load_library() -> ctypes.CDLL:
     lib.lukv_select_compact.argtypes = [CP, P, P, P, P, P, I64, P, P, P, P, P, I64, P]
     lib.lukv_evict.argtypes = [CP, P, P, P, I32, P, P, P, P, ctypes.POINTER(I64),
                                P, P, P, P, P, P, P, P, I64, P]
-    for name in EXPORTS[:-1]:
-        getattr(lib, name).restype = ctypes.c_int
+    lib.lukv_set_stage_events.argtypes = [ctypes.POINTER(ctypes.c_void_p), I32]
+    lib.lukv_stage_name.argtypes = [I32]
+    lib.lukv_stage_name.restype = ctypes.c_char_p
+    for name in EXPORTS:
+        if name not in ("lukv_strerror", "lukv_stage_name"):
+            getattr(lib, name).restype = ctypes.c_int
     lib.lukv_strerror.argtypes = [ctypes.c_int]
     lib.lukv_strerror.restype = ctypes.c_char_p
     _lib = lib
@@ -214,3 +221,15 @@ def lukv_evict(cfg: Config, q_win, k, v, n_grid: int, curves, knots, b_min, b_ma
                                      _ptr(budgets), _ptr(offsets), _ptr(kept_idx), _ptr(k_out),
                                      _ptr(v_out), _ptr(pooled), _ptr(status), _ptr(ws), ws.numel(),
                                      _stream(stream)), "lukv_evict")
+
+
+def lukv_set_stage_events(events) -> None:
+    """events: a ctypes array of hipEvent_t handles (kept alive by the caller), or None to stop."""
+    if events is None:
+        _check(load_library().lukv_set_stage_events(None, 0), "lukv_set_stage_events")
+    else:
+        _check(load_library().lukv_set_stage_events(events, len(events)), "lukv_set_stage_events")
+
+
+def lukv_stage_name(stage: int) -> str:
+    return load_library().lukv_stage_name(int(stage)).decode()
