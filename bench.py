@@ -121,16 +121,19 @@ def main() -> int:
         step(i)
     lukv.lukv_set_stage_events(None)
     torch.cuda.synchronize()
-    stage_ms = np.zeros(n_ev - 1)
+    # lukv_evict records these stages (the allocation rides inside the two score kernels)
+    names = [lukv.lukv_stage_name(j) for j in range(n_ev)]
+    used = [names.index(n) for n in ("score_stats", "score_accum", "sel_hist", "sel_tail", "sel_emit", "end")]
+    stage_ms = np.zeros(len(used) - 1)
     for arr in ev_sets:
-        for j in range(n_ev - 1):
+        for i, (a, b) in enumerate(zip(used[:-1], used[1:])):
             ms = ctypes.c_float()
-            assert hip.hipEventElapsedTime(ctypes.byref(ms), arr[j], arr[j + 1]) == 0
-            stage_ms[j] += ms.value
+            assert hip.hipEventElapsedTime(ctypes.byref(ms), arr[a], arr[b]) == 0
+            stage_ms[i] += ms.value
         for j in range(n_ev):
             hip.hipEventDestroy(arr[j])
     stage_ms /= n_timed
-    stages = {lukv.lukv_stage_name(j): round(float(stage_ms[j]) * 1e3, 2) for j in range(n_ev - 1)}
+    stages = {names[a]: round(float(stage_ms[i]) * 1e3, 2) for i, a in enumerate(used[:-1])}
 
     # algorithmic bytes per launch of the two streaming score kernels (8B/32k layer)
     esz = 2

@@ -103,7 +103,7 @@ int lukv_score(const lukv_config* cfg, const void* q_win, const void* k, float* 
  *   budgets device int32 [n_problems*n_heads]      (sum over a problem = B_total when feasible)
  *   offsets device int64 [n_problems*n_heads + 1]  exclusive prefix sum of budgets
  *   status  device int32 [n_problems]: 0, or LUKV_ST_INFEASIBLE (then budgets = b_min)
- * Limits: n_problems <= LUKV_MAX_SEQS, 2 <= n_grid. */
+ * Limits: n_problems <= LUKV_MAX_SEQS, 2 <= n_grid <= 1980. */
 int lukv_allocate(int32_t n_problems, int32_t n_heads, int32_t n_grid,
                   const float* curves, const int32_t* knots,
                   const int32_t* b_min, const int32_t* b_max, const int64_t* B_total,
@@ -143,10 +143,10 @@ int lukv_evict(const lukv_config* cfg, const void* q_win, const void* k, const v
  * by the caller, passed as void*) on its stream immediately before stage i, and lukv_evict records
  * events[LUKV_STAGE_END] after its last stage; entries that are NULL or beyond n_events are
  * skipped.  The array must stay valid until lukv_set_stage_events(NULL, 0).  Stage order:
- * clear, allocate, score_stats, score_accum, pool, sel_hist0, sel_hist1, sel_hist2, sel_count,
- * sel_emit, end (lukv_stage_name gives the same names; "" when out of range). */
-#define LUKV_STAGE_END 10
-#define LUKV_NUM_STAGE_EVENTS 11
+ * allocate (stand-alone call only), score_stats, score_accum, pool (lukv_score only), sel_hist,
+ * sel_tail, sel_emit, end (lukv_stage_name gives the same names; "" when out of range). */
+#define LUKV_STAGE_END 7
+#define LUKV_NUM_STAGE_EVENTS 8
 int lukv_set_stage_events(void* const* events, int32_t n_events);
 const char* lukv_stage_name(int32_t stage);
 

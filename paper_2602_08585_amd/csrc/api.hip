@@ -2,6 +2,7 @@
 #include <math.h>
 #include <string.h>
 
+#include "alloc_device.hpp"
 #include "lukv_internal.hpp"
 
 namespace lukv {
@@ -64,6 +65,9 @@ int validate_config(const lukv_config* cfg, HostCfg* out) {
   }
   g.total_tokens = out->seq.cu[cfg->n_seqs];
   out->max_len = max_len;
+  // keys per score workgroup: at most 64 chunks per head (pass B merges them in its prologue)
+  g.chunk_keys = 512;
+  while ((max_len + g.chunk_keys - 1) / g.chunk_keys > 64) g.chunk_keys *= 2;
   out->n_hi = cfg->n_seqs * g.n_layers * g.n_kv_heads;
   return LUKV_OK;
 }
@@ -83,48 +87,27 @@ WsLayout make_layout(const HostCfg& hc, int32_t n_grid, bool alloc_only) {
   memset(&w, 0, sizeof(w));
   const Geom& g = hc.g;
   w.n_hi = hc.n_hi;
-  w.max_chunks = (hc.max_len + kChunkKeys - 1) / kChunkKeys;
+  w.max_chunks = g.chunk_keys > 0 ? (hc.max_len + g.chunk_keys - 1) / g.chunk_keys : 0;
+  w.max_blocks = (hc.max_len + kEmitElems - 1) / kEmitElems;
   w.max_slices = (hc.max_len + kSliceElems - 1) / kSliceElems;
   w.rows_padded = g.row_blocks * 32;
   int64_t off = 0;
   auto take = [&](int64_t bytes) { const int64_t o = off; off = align_up(off + bytes, 256); return o; };
-  w.zero_off = off;
   const int64_t n_sel = alloc_only ? 0 : w.n_hi;
-  w.stats_cnt = take(n_sel * 4);
-  w.sel_cnt = take(n_sel * 4 * 4);
-  w.hist = take(n_sel * kRadixPasses * kHistBins * 4);
-  w.alloc_cnt = take(64 * 4);
-  w.zero_bytes = off - w.zero_off;
+  w.alloc_meta = take(LUKV_MAX_SEQS * 4 * 8);
+  w.hist = take(n_sel * w.max_slices * (kHistBins / 2) * 4);
   w.partial = take((int64_t)w.n_hi * w.max_chunks * w.rows_padded * 8);
-  w.rowc = take((int64_t)w.n_hi * w.rows_padded * 4);
   const int64_t score_bytes = (int64_t)g.n_layers * g.n_kv_heads * g.total_tokens * 4;
   w.raw = take(score_bytes);
   w.pooled = take(score_bytes);
   w.sel_state = take(n_sel * 16);
-  w.slice_cnt = take(n_sel * w.max_slices * 8);
+  w.slice_cnt = take(n_sel * w.max_blocks * 8);
   const int64_t nseg = (int64_t)hc.n_hi * (n_grid > 0 ? n_grid : 0);
   w.hull = take(nseg * 4);
   w.seg_key = take(nseg * 8);
   w.seg_w = take(nseg * 4);
   w.total = off;
   return w;
-}
-
-// Zero the counters and histograms of the workspace, and one caller status word if given
-// (a fill kernel rather than a memset node, so that callers may capture the call in a graph).
-__global__ __launch_bounds__(256) void clear_kernel(uint4* p, int64_t n16, int32_t* word) {
-  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (i < n16) p[i] = make_uint4(0, 0, 0, 0);
-  if (i == 0 && word) *word = 0;
-}
-
-int launch_clear(const WsLayout& lay, char* ws, int32_t* word, hipStream_t st) {
-  const int64_t n16 = lay.zero_bytes / 16;
-  const int blocks = (int)((n16 + 255) / 256);
-  stage_mark(kStClear, st);
-  hipLaunchKernelGGL(clear_kernel, dim3(blocks), dim3(256), 0, st,
-                     reinterpret_cast<uint4*>(ws + lay.zero_off), n16, word);
-  return check_launch();
 }
 
 static void* const* g_stage_events = nullptr;
@@ -156,7 +139,7 @@ using namespace lukv;
 extern "C" {
 
 int lukv_workspace_bytes(const lukv_config* cfg, int32_t n_grid, int64_t* bytes) {
-  if (!bytes || n_grid < 0) return LUKV_EINVAL;
+  if (!bytes || n_grid < 0 || n_grid > kMaxGrid) return LUKV_EINVAL;
   HostCfg hc;
   const int rc = validate_config(cfg, &hc);
   if (rc) return rc;
@@ -166,7 +149,8 @@ int lukv_workspace_bytes(const lukv_config* cfg, int32_t n_grid, int64_t* bytes)
 
 int lukv_allocate_workspace_bytes(int32_t n_problems, int32_t n_heads, int32_t n_grid,
                                   int64_t* bytes) {
-  if (!bytes || n_problems < 1 || n_problems > LUKV_MAX_SEQS || n_heads < 1 || n_grid < 2)
+  if (!bytes || n_problems < 1 || n_problems > LUKV_MAX_SEQS || n_heads < 1 || n_grid < 2 ||
+      n_grid > kMaxGrid)
     return LUKV_EINVAL;
   if ((int64_t)n_problems * n_heads > (1 << 24)) return LUKV_EINVAL;
   *bytes = alloc_only_layout(n_problems, n_heads, n_grid).total;
@@ -182,15 +166,16 @@ int lukv_score(const lukv_config* cfg, const void* q_win, const void* k, float* 
   const WsLayout lay = make_layout(hc, 0, false);
   if ((rc = check_ws(lay, ws, ws_bytes))) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  if ((rc = launch_clear(lay, (char*)ws, nullptr, st))) return rc;
-  return launch_score(hc, lay, q_win, k, pooled, (char*)ws, st);
+  if ((rc = launch_score_raw(hc, lay, q_win, k, nullptr, (char*)ws, st))) return rc;
+  return launch_pool(hc, lay, pooled, (char*)ws, st);
 }
 
 int lukv_allocate(int32_t n_problems, int32_t n_heads, int32_t n_grid, const float* curves,
                   const int32_t* knots, const int32_t* b_min, const int32_t* b_max,
                   const int64_t* B_total, int32_t* budgets, int64_t* offsets, int32_t* status,
                   void* ws, int64_t ws_bytes, void* stream) {
-  if (n_problems < 1 || n_problems > LUKV_MAX_SEQS || n_heads < 1 || n_grid < 2) return LUKV_EINVAL;
+  if (n_problems < 1 || n_problems > LUKV_MAX_SEQS || n_heads < 1 || n_grid < 2 || n_grid > kMaxGrid)
+    return LUKV_EINVAL;
   if ((int64_t)n_problems * n_heads > (1 << 24)) return LUKV_EINVAL;
   if (!curves || !knots || !b_min || !b_max || !B_total || !budgets || !offsets || !status)
     return LUKV_EINVAL;
@@ -203,9 +188,8 @@ int lukv_allocate(int32_t n_problems, int32_t n_heads, int32_t n_grid, const flo
   int rc;
   if ((rc = check_ws(lay, ws, ws_bytes))) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  if ((rc = launch_clear(lay, (char*)ws, nullptr, st))) return rc;
-  return launch_allocate(n_problems, n_heads, n_grid, curves, knots, b_min, b_max, B_total, budgets,
-                         offsets, status, lay, (char*)ws, st);
+  return launch_allocate(make_alloc_io(n_problems, n_heads, n_grid, curves, knots, b_min, b_max, B_total,
+                                       budgets, offsets, status, lay, (char*)ws), st);
 }
 
 int lukv_select_compact(const lukv_config* cfg, const float* pooled, const int32_t* budgets,
@@ -222,9 +206,8 @@ int lukv_select_compact(const lukv_config* cfg, const float* pooled, const int32
   const WsLayout lay = make_layout(hc, 0, false);
   if ((rc = check_ws(lay, ws, ws_bytes))) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  if ((rc = launch_clear(lay, (char*)ws, status, st))) return rc;
-  return launch_select_compact(hc, lay, pooled, budgets, offsets, k, v, kept_idx, k_out, v_out,
-                               out_rows, status, (char*)ws, st);
+  return launch_select_compact(hc, lay, pooled, false, nullptr, budgets, const_cast<int64_t*>(offsets),
+                               false, k, v, kept_idx, k_out, v_out, out_rows, status, (char*)ws, st);
 }
 
 int lukv_evict(const lukv_config* cfg, const void* q_win, const void* k, const void* v,
@@ -235,7 +218,7 @@ int lukv_evict(const lukv_config* cfg, const void* q_win, const void* k, const v
   HostCfg hc;
   int rc = validate_config(cfg, &hc);
   if (rc) return rc;
-  if (n_grid < 2) return LUKV_EINVAL;
+  if (n_grid < 2 || n_grid > kMaxGrid) return LUKV_EINVAL;
   if (!q_win || !k || !v || !curves || !knots || !b_min || !b_max || !B_total || !budgets ||
       !offsets || !kept_idx || !k_out || !v_out || !status)
     return LUKV_EINVAL;
@@ -252,14 +235,14 @@ int lukv_evict(const lukv_config* cfg, const void* q_win, const void* k, const v
   char* w = (char*)ws;
   float* scores = pooled ? pooled : reinterpret_cast<float*>(w + lay.pooled);
   int32_t* sel_status = status + cfg->n_seqs;
-  if ((rc = launch_clear(lay, w, sel_status, st))) return rc;
+  // the allocation never looks at scores: its two phases ride along as extra workgroups of
+  // the two score kernels; selection pools the raw metric on the fly
   const int n_heads = hc.g.n_layers * hc.g.n_kv_heads;
-  if ((rc = launch_allocate(cfg->n_seqs, n_heads, n_grid, curves, knots, b_min, b_max, B_total,
-                            budgets, offsets, status, lay, w, st)))
-    return rc;
-  if ((rc = launch_score(hc, lay, q_win, k, scores, w, st))) return rc;
-  rc = launch_select_compact(hc, lay, scores, budgets, offsets, k, v, kept_idx, k_out, v_out,
-                             out_rows, sel_status, w, st);
+  const AllocIO aio = make_alloc_io(cfg->n_seqs, n_heads, n_grid, curves, knots, b_min, b_max, B_total,
+                                    budgets, offsets, status, lay, w);
+  if ((rc = launch_score_raw(hc, lay, q_win, k, &aio, w, st))) return rc;
+  rc = launch_select_compact(hc, lay, reinterpret_cast<const float*>(w + lay.raw), true, scores, budgets,
+                             offsets, true, k, v, kept_idx, k_out, v_out, out_rows, sel_status, w, st);
   stage_mark(kStEnd, st);
   return rc;
 }
@@ -273,8 +256,7 @@ int lukv_set_stage_events(void* const* events, int32_t n_events) {
 
 const char* lukv_stage_name(int32_t stage) {
   static const char* const names[kNumStageEvents] = {
-      "clear", "allocate", "score_stats", "score_accum", "pool", "sel_hist0", "sel_hist1",
-      "sel_hist2", "sel_count", "sel_emit", "end"};
+      "allocate", "score_stats", "score_accum", "pool", "sel_hist", "sel_tail", "sel_emit", "end"};
   return stage >= 0 && stage < kNumStageEvents ? names[stage] : "";
 }
 

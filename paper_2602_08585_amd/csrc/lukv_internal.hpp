@@ -8,11 +8,15 @@
 
 namespace lukv {
 
+// 16 bytes as a first-class vector.  Register arrays must use this, not the uint4 struct:
+// arrays of the struct type are not promoted to registers and end up in scratch memory.
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+
 // ---- tiling constants -------------------------------------------------------------------
-constexpr int kChunkKeys = 512;    // keys one workgroup of the score kernels streams
-constexpr int kSliceElems = 1024;  // scores one workgroup of the selection kernels owns
-constexpr int kHistBins = 2048;    // bins of one radix pass
-constexpr int kRadixPasses = 3;    // digits of 11, 11 and 10 bits, most significant first
+constexpr int kSliceElems = 1024;  // scores one workgroup of the selection histogram owns
+constexpr int kEmitElems = 256;    // scores one workgroup of the emit/gather kernel owns
+constexpr int kHistBins = 2048;    // bins of the widest radix digit (11, 11, 10 bits)
+constexpr int kMaxGrid = 1980;     // utility-curve grid points (hull stack lives in LDS)
 constexpr int kMaxRows = 512;      // G * window upper bound
 
 // Packed-sequence table passed to kernels by value: sequence boundaries plus the first tile
@@ -32,6 +36,7 @@ struct Geom {
   int32_t row_groups;  // 1, 2 or 4 wave groups share the row blocks
   int32_t blocks_per_group;
   int32_t total_tokens;
+  int32_t chunk_keys;  // keys one workgroup of the score kernels streams (multiple of 128)
   int64_t sl, sh, st;     // K/V strides (elements)
   int64_t qsl, qsh, qst;  // Q strides (elements)
   float scale_log2e;      // softmax scale * log2(e)
@@ -40,22 +45,18 @@ struct Geom {
 
 // Byte offsets into the caller's workspace.
 struct WsLayout {
-  int64_t zero_off, zero_bytes;  // region cleared at the start of every call
-  int64_t stats_cnt;             // u32 [n_hi]
-  int64_t sel_cnt;               // u32 [n_hi * 4]
-  int64_t hist;                  // u32 [n_hi * 3 * kHistBins]
-  int64_t alloc_cnt;             // u32 [64]
+  int64_t alloc_meta;            // i64 [LUKV_MAX_SEQS * 4]
+  int64_t hist;                  // u32 [n_hi * max_slices * kHistBins / 2] packed 16-bit counts
   int64_t partial;               // float2 [n_hi * max_chunks * rows_padded]
-  int64_t rowc;                  // float [n_hi * rows_padded]
   int64_t raw;                   // float [n_layers * n_kv_heads * total_tokens]
   int64_t pooled;                // float, same shape
   int64_t sel_state;             // uint4 [n_hi]
-  int64_t slice_cnt;             // uint2 [n_hi * max_slices]
+  int64_t slice_cnt;             // uint2 [n_hi * max_blocks]
   int64_t hull;                  // i32 [n_problems * n_heads * n_grid]
   int64_t seg_key;               // u64 [n_problems * n_heads * n_grid]
   int64_t seg_w;                 // u32 [n_problems * n_heads * n_grid]
   int64_t total;
-  int32_t n_hi, max_chunks, max_slices, rows_padded;
+  int32_t n_hi, max_chunks, max_slices, max_blocks, rows_padded;
 };
 
 struct HostCfg {
@@ -70,21 +71,24 @@ WsLayout make_layout(const HostCfg& hc, int32_t n_grid, bool alloc_only);
 SeqTab tiles_for(const SeqTab& seq, int tile, int shrink);  // tiles over (L_s - shrink) tokens
 
 // Launchers (enqueue only; return a LUKV_* code).
-int launch_clear(const WsLayout& lay, char* ws, int32_t* word, hipStream_t st);
-int launch_score(const HostCfg& hc, const WsLayout& lay, const void* q, const void* k,
-                 float* pooled_out, char* ws, hipStream_t st);
-int launch_select_compact(const HostCfg& hc, const WsLayout& lay, const float* pooled,
-                          const int32_t* budgets, const int64_t* offsets, const void* k,
-                          const void* v, int32_t* kept_idx, void* k_out, void* v_out,
+struct AllocIO;
+// raw (unpooled) metric into the workspace; aio != NULL also runs the allocation alongside
+int launch_score_raw(const HostCfg& hc, const WsLayout& lay, const void* q, const void* k,
+                     const AllocIO* aio, char* ws, hipStream_t st);
+int launch_pool(const HostCfg& hc, const WsLayout& lay, float* pooled_out, char* ws, hipStream_t st);
+int launch_select_compact(const HostCfg& hc, const WsLayout& lay, const float* scores_in, bool pool,
+                          float* pooled_out, const int32_t* budgets, int64_t* offsets,
+                          bool make_offsets, const void* k, const void* v, int32_t* kept_idx, void* k_out, void* v_out,
                           int64_t out_rows, int32_t* status, char* ws, hipStream_t st);
-int launch_allocate(int32_t n_problems, int32_t n_heads, int32_t n_grid, const float* curves,
-                    const int32_t* knots, const int32_t* b_min, const int32_t* b_max,
-                    const int64_t* B_total, int32_t* budgets, int64_t* offsets, int32_t* status,
-                    const WsLayout& lay, char* ws, hipStream_t st);
+AllocIO make_alloc_io(int32_t n_problems, int32_t n_heads, int32_t n_grid, const float* curves,
+                      const int32_t* knots, const int32_t* b_min, const int32_t* b_max,
+                      const int64_t* B_total, int32_t* budgets, int64_t* offsets, int32_t* status,
+                      const WsLayout& lay, char* ws);
+int launch_allocate(const AllocIO& io, hipStream_t st);
 
 // Optional instrumentation (lukv_set_stage_events): record the caller's event for a stage.
-enum Stage { kStClear = 0, kStAllocate, kStStats, kStAccum, kStPool, kStHist0, kStHist1, kStHist2,
-             kStCount, kStEmit, kStEnd, kNumStageEvents };
+enum Stage { kStAllocate = 0, kStStats, kStAccum, kStPool, kStHist, kStTail, kStEmit, kStEnd,
+             kNumStageEvents };
 void stage_mark(int stage, hipStream_t st);
 
 inline int check_launch() {

@@ -9,12 +9,24 @@
 //            c_r = max_r * a + log2(sum_r), a = scale * log2(e).
 //   accum  - S = Q * K_tile^T, so that a lane owns one key column; P = exp2(S*a - c_r) is
 //            summed over the G*w rows in registers and written as the unpooled metric.
-// A third, tiny kernel applies the clipped max-pool and the +inf of forced positions.
+// A third, tiny kernel applies the clipped max-pool and the +inf of forced positions when
+// the scores are wanted on their own (lukv_score); the fused path pools inside selection.
+//
+// A workgroup (4 waves) streams a chunk of keys in tiles of 128/RG keys: the next tile is
+// in flight from HBM into registers while the current one, staged in LDS with a 16-byte row
+// pad (conflict-free 128-bit reads), feeds the matrix cores.  RG wave groups share the row
+// blocks when G*w > 32*NBM.
 //
 // Matrix-core operand layout (v_mfma_f32_32x32x16_bf16 / 32x32x2_f32): lane l supplies row
 // l%32 of its operand and the k-slice selected by l/32; both operands use the same rule
 // "half hf = l/32 owns elements [hf*D/2, (hf+1)*D/2) of the row", so any internal ordering
 // of k is the same on both sides.  Output: acc[v] is row 8*(v/4) + 4*(l/32) + v%4, column l%32.
+//
+// When the fused path asks for it, the first blockIdx.x values of the two kernels run the
+// two phases of the budget allocation instead of scoring (they do not depend on scores).
+#include <string.h>
+
+#include "alloc_device.hpp"
 #include "lukv_internal.hpp"
 
 namespace lukv {
@@ -24,7 +36,7 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 template <bool F32>
-__device__ __forceinline__ f32x16 mma(uint4 a, uint4 b, f32x16 c) {
+__device__ __forceinline__ f32x16 mma(u32x4 a, u32x4 b, f32x16 c) {
   if constexpr (!F32) {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
                                                    __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
@@ -38,37 +50,48 @@ __device__ __forceinline__ f32x16 mma(uint4 a, uint4 b, f32x16 c) {
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-template <bool F32, int D>
+template <bool F32, int D, int RG>
 struct Tile {
   static constexpr int kEsize = F32 ? 4 : 2;
   static constexpr int kRowBytes = D * kEsize;
   static constexpr int kRowU4 = kRowBytes / 16;        // 16-byte units per row
   static constexpr int kHalfU4 = kRowU4 / 2;           // units one lane half consumes
   static constexpr int kLdsRowU4 = kRowU4 + 1;         // +16 B pad: conflict-free b128 reads
-  static constexpr int kMaxKeys = 128;
+  static constexpr int kKeys = 128 / RG;               // keys per tile
+  static constexpr int kWaveCols = 4 / RG;             // 32-key subtiles per tile
+  static constexpr int kLoads = kKeys * kRowU4 / 256;  // 16-byte loads per thread per tile
+  static constexpr int kRowStep = 256 / kRowU4;        // rows between a thread's loads
+  static_assert(kLoads >= 1, "tile too small for 256 threads");
 };
 
-// Copy `keys` rows of K (sequence-relative rows j0.., clamped to L-1) into LDS.
-template <bool F32, int D>
-__device__ __forceinline__ void load_k_tile(uint4* lds, const char* kbase, int64_t tok_stride_bytes,
-                                            int j0, int keys, int L) {
-  using T = Tile<F32, D>;
-  const int n = keys * T::kRowU4;
-  for (int idx = threadIdx.x; idx < n; idx += 256) {
-    const int row = idx / T::kRowU4, col = idx % T::kRowU4;
-    int j = j0 + row;
+// One thread's share of a K tile (plain local arrays: they must stay in registers so that
+// the loads of the next tile are in flight while the current one is consumed).
+// k_issue starts the loads (rows clamped to L-1), k_commit stores them to LDS.
+template <bool F32, int D, int RG, int NL>
+__device__ __forceinline__ void k_issue(u32x4 (&pre)[NL], const char* base, int64_t tok_bytes,
+                                        int row0, int j0, int L) {
+  using T = Tile<F32, D, RG>;
+#pragma unroll
+  for (int i = 0; i < NL; ++i) {
+    int j = j0 + row0 + i * T::kRowStep;
     j = j < L ? j : L - 1;
-    const uint4 val = *reinterpret_cast<const uint4*>(kbase + (int64_t)j * tok_stride_bytes + col * 16);
-    lds[row * T::kLdsRowU4 + col] = val;
+    pre[i] = *reinterpret_cast<const u32x4*>(base + (int64_t)j * tok_bytes);
   }
+}
+
+template <bool F32, int D, int RG, int NL>
+__device__ __forceinline__ void k_commit(const u32x4 (&pre)[NL], u32x4* lds, int lds_off) {
+  using T = Tile<F32, D, RG>;
+#pragma unroll
+  for (int i = 0; i < NL; ++i) lds[lds_off + i * T::kRowStep * T::kLdsRowU4] = pre[i];
 }
 
 // Window-query rows of this wave's row blocks, as matrix-core operands held in registers.
 template <bool F32, int D, int NBM, int HU>
-__device__ __forceinline__ void load_q(uint4 (&qreg)[NBM][HU], const Geom& g,
-                                       const char* q, int layer, int kvh, int seq, int blk0,
-                                       int nb_count, int lane) {
-  using T = Tile<F32, D>;
+__device__ __forceinline__ void load_q(u32x4 (&qreg)[NBM][HU], const Geom& g, const char* q,
+                                       int layer, int kvh, int seq, int blk0, int nb_count,
+                                       int lane) {
+  constexpr int kEsize = F32 ? 4 : 2;
   const int hf = lane >> 5;
 #pragma unroll
   for (int nb = 0; nb < NBM; ++nb) {
@@ -76,11 +99,11 @@ __device__ __forceinline__ void load_q(uint4 (&qreg)[NBM][HU], const Geom& g,
     const bool live = nb < nb_count && r < g.rows;
     const int gq = live ? r / g.window : 0, i = live ? r % g.window : 0;
     const char* p = q + ((int64_t)layer * g.qsl + (int64_t)(kvh * g.group + gq) * g.qsh +
-                         (int64_t)(seq * g.window + i) * g.qst) * T::kEsize +
-                    hf * (T::kRowBytes / 2);
+                         (int64_t)(seq * g.window + i) * g.qst) * kEsize +
+                    hf * (D * kEsize / 2);
 #pragma unroll
-    for (int s = 0; s < T::kHalfU4; ++s)
-      qreg[nb][s] = live ? reinterpret_cast<const uint4*>(p)[s] : make_uint4(0, 0, 0, 0);
+    for (int s = 0; s < HU; ++s)
+      qreg[nb][s] = live ? reinterpret_cast<const u32x4*>(p)[s] : u32x4{0u, 0u, 0u, 0u};
   }
 }
 
@@ -92,31 +115,46 @@ __device__ __forceinline__ void merge_stats(float& m, float& z, float m2, float 
 }
 
 // ---- pass A: softmax statistics ----------------------------------------------------------
-template <bool F32, int D, int NBM>
-__global__ __launch_bounds__(256) void score_stats_kernel(Geom g, SeqTab tab, const char* q,
+template <bool F32, int D, int NBM, int RG>
+__global__ __launch_bounds__(256) void score_stats_kernel(Geom g, SeqTab tab, AllocIO aio,
+                                                          int n_alloc_blocks, const char* q,
                                                           const char* k, float2* partial,
-                                                          float* rowc, unsigned* counter,
                                                           int max_chunks, int rows_padded) {
-  using T = Tile<F32, D>;
-  __shared__ uint4 ktile[T::kMaxKeys * T::kLdsRowU4];
+  using T = Tile<F32, D, RG>;
+  // at least 32 KiB: the allocation phase borrows the tile as scratch (hull stacks)
+  constexpr int kTileU4 = T::kKeys * T::kLdsRowU4 > 2048 ? T::kKeys * T::kLdsRowU4 : 2048;
+  __shared__ u32x4 ktile[kTileU4];
   __shared__ float2 wstat[4][NBM][32];
-  __shared__ int is_last;
 
+  if ((int)blockIdx.x < n_alloc_blocks) {
+    if (blockIdx.y == 0 && blockIdx.z == 0)
+      alloc_phase_a(aio, blockIdx.x, reinterpret_cast<char*>(ktile), (int)sizeof(ktile));
+    return;
+  }
   int seq, ch;
-  find_tile(tab, blockIdx.x, seq, ch);
+  find_tile(tab, blockIdx.x - n_alloc_blocks, seq, ch);
   const int kvh = blockIdx.y, layer = blockIdx.z;
   const int tok0 = tab.cu[seq], L = tab.cu[seq + 1] - tok0, P = L - g.window;
   const int hi = (seq * g.n_layers + layer) * g.n_kv_heads + kvh;
-  const int n_chunks = tab.tile0[seq + 1] - tab.tile0[seq];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, hf = lane >> 5;
-  const int n_kt = 4 / g.row_groups, kt = wave % n_kt, rg = wave / n_kt;
-  const int keys_per_iter = 32 * n_kt;
+  constexpr int n_kt = T::kWaveCols;
+  const int kt = wave % n_kt, rg = wave / n_kt;
   const int blk0 = rg * g.blocks_per_group;
   int nb_count = g.row_blocks - blk0;
   nb_count = nb_count < 0 ? 0 : (nb_count > g.blocks_per_group ? g.blocks_per_group : nb_count);
   const float a = g.scale_log2e;
 
-  uint4 qreg[NBM][T::kHalfU4];
+  const char* kbase = k + ((int64_t)layer * g.sl + (int64_t)kvh * g.sh + (int64_t)tok0 * g.st) * T::kEsize;
+  const int j_begin = ch * g.chunk_keys;
+  const int j_end = min(L, j_begin + g.chunk_keys);
+  const int64_t tok_bytes = g.st * T::kEsize;
+  const int ld_row0 = threadIdx.x / T::kRowU4, ld_col = threadIdx.x % T::kRowU4;
+  const int ld_lds = ld_row0 * T::kLdsRowU4 + ld_col;
+  const char* ld_base = kbase + ld_col * 16;
+  u32x4 pre[T::kLoads];
+  k_issue<F32, D, RG, T::kLoads>(pre, ld_base, tok_bytes, ld_row0, j_begin, L);
+
+  u32x4 qreg[NBM][T::kHalfU4];
   load_q<F32, D, NBM, T::kHalfU4>(qreg, g, q, layer, kvh, seq, blk0, nb_count, lane);
 
   // window row index of this lane's query in every block (for the causal range)
@@ -128,46 +166,43 @@ __global__ __launch_bounds__(256) void score_stats_kernel(Geom g, SeqTab tab, co
 #pragma unroll
   for (int nb = 0; nb < NBM; ++nb) { m[nb] = -INFINITY; z[nb] = 0.f; }
 
-  const char* kbase = k + ((int64_t)layer * g.sl + (int64_t)kvh * g.sh + (int64_t)tok0 * g.st) * T::kEsize;
-  const int64_t tok_bytes = g.st * T::kEsize;
-  const int j_begin = ch * kChunkKeys;
-  const int j_end = min(L, j_begin + kChunkKeys);
-
-  for (int j0 = j_begin; j0 < j_end; j0 += keys_per_iter) {
+  for (int j0 = j_begin; j0 < j_end; j0 += T::kKeys) {
+    __syncthreads();               // every wave is done reading the previous tile
+    k_commit<F32, D, RG, T::kLoads>(pre, ktile, ld_lds);
     __syncthreads();
-    load_k_tile<F32, D>(ktile, kbase, tok_bytes, j0, keys_per_iter, L);
-    __syncthreads();
-    const int jw = j0 + 32 * kt;           // first key of this wave's 32-key subtile
-    if (jw >= j_end) continue;             // uniform per wave; barriers above are unconditional
-    uint4 kreg[T::kHalfU4];
-    const uint4* src = ktile + (32 * kt + (lane & 31)) * T::kLdsRowU4 + hf * T::kHalfU4;
+    if (j0 + T::kKeys < j_end) k_issue<F32, D, RG, T::kLoads>(pre, ld_base, tok_bytes, ld_row0, j0 + T::kKeys, L);
+    const int jw = j0 + 32 * kt;   // first key of this wave's 32-key subtile
+    if (jw < j_end) {              // wave-uniform
+      u32x4 kreg[T::kHalfU4];
+      const u32x4* src = ktile + (32 * kt + (lane & 31)) * T::kLdsRowU4 + hf * T::kHalfU4;
 #pragma unroll
-    for (int s = 0; s < T::kHalfU4; ++s) kreg[s] = src[s];
-    const bool need_mask = jw + 32 > P;
+      for (int s = 0; s < T::kHalfU4; ++s) kreg[s] = src[s];
+      const bool need_mask = jw + 32 > P;
 #pragma unroll
-    for (int nb = 0; nb < NBM; ++nb) {
-      if (nb < nb_count) {
-        f32x16 acc = {0};
+      for (int nb = 0; nb < NBM; ++nb) {
+        if (nb < nb_count) {
+          f32x16 acc = {0};
 #pragma unroll
-        for (int s = 0; s < T::kHalfU4; ++s) acc = mma<F32>(kreg[s], qreg[nb][s], acc);
-        if (need_mask) {
+          for (int s = 0; s < T::kHalfU4; ++s) acc = mma<F32>(kreg[s], qreg[nb][s], acc);
+          if (need_mask) {
 #pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const int j = jw + 8 * (v >> 2) + 4 * hf + (v & 3);
-            if (j >= L || j > P + wrow[nb]) acc[v] = -INFINITY;
+            for (int v = 0; v < 16; ++v) {
+              const int j = jw + 8 * (v >> 2) + 4 * hf + (v & 3);
+              if (j >= L || j > P + wrow[nb]) acc[v] = -INFINITY;
+            }
           }
+          float tm = acc[0];
+#pragma unroll
+          for (int v = 1; v < 16; ++v) tm = fmaxf(tm, acc[v]);
+          const float mn = fmaxf(m[nb], tm);
+          const float ms = mn == -INFINITY ? 0.f : mn;
+          float zz = z[nb] * fast_exp2((m[nb] - ms) * a);
+          const float off = -ms * a;
+#pragma unroll
+          for (int v = 0; v < 16; ++v) zz += fast_exp2(fmaf(acc[v], a, off));
+          z[nb] = zz;
+          m[nb] = mn;
         }
-        float tm = acc[0];
-#pragma unroll
-        for (int v = 1; v < 16; ++v) tm = fmaxf(tm, acc[v]);
-        const float mn = fmaxf(m[nb], tm);
-        const float ms = mn == -INFINITY ? 0.f : mn;
-        float zz = z[nb] * fast_exp2((m[nb] - ms) * a);
-        const float off = -ms * a;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) zz += fast_exp2(fmaf(acc[v], a, off));
-        z[nb] = zz;
-        m[nb] = mn;
       }
     }
   }
@@ -184,75 +219,109 @@ __global__ __launch_bounds__(256) void score_stats_kernel(Geom g, SeqTab tab, co
   for (int r = threadIdx.x; r < rows_padded; r += 256) {
     const int blk = r >> 5, grp = blk / g.blocks_per_group, nb = blk - grp * g.blocks_per_group;
     float mm = -INFINITY, zz = 0.f;
-    if (grp < g.row_groups) {
-      for (int t = 0; t < n_kt; ++t) {
-        const float2 st = wstat[grp * n_kt + t][nb][r & 31];
-        merge_stats(mm, zz, st.x, st.y, a);
-      }
+    for (int t = 0; t < n_kt; ++t) {
+      const float2 st = wstat[grp * n_kt + t][nb][r & 31];
+      merge_stats(mm, zz, st.x, st.y, a);
     }
     partial[((int64_t)hi * max_chunks + ch) * rows_padded + r] = make_float2(mm, zz);
-  }
-  __threadfence();
-  __syncthreads();
-  if (threadIdx.x == 0) is_last = atomicAdd(&counter[hi], 1u) == (unsigned)(n_chunks - 1);
-  __syncthreads();
-  if (!is_last) return;
-  __threadfence();
-  for (int r = threadIdx.x; r < rows_padded; r += 256) {
-    float mm = -INFINITY, zz = 0.f;
-    for (int c2 = 0; c2 < n_chunks; ++c2) {
-      const float* pp = reinterpret_cast<const float*>(&partial[((int64_t)hi * max_chunks + c2) * rows_padded + r]);
-      merge_stats(mm, zz, __builtin_nontemporal_load(pp), __builtin_nontemporal_load(pp + 1), a);
-    }
-    // padded rows never contribute: +inf makes exp2(S*a - c) vanish in pass B
-    rowc[(int64_t)hi * rows_padded + r] = r < g.rows ? mm * a + log2f(zz) : INFINITY;
   }
 }
 
 // ---- pass B: normalised window sums ------------------------------------------------------
-template <bool F32, int D, int NBM>
-__global__ __launch_bounds__(256) void score_accum_kernel(Geom g, SeqTab tab, const char* q,
-                                                          const char* k, const float* rowc,
-                                                          float* raw, int rows_padded) {
-  using T = Tile<F32, D>;
-  __shared__ uint4 ktile[T::kMaxKeys * T::kLdsRowU4];
+template <bool F32, int D, int NBM, int RG>
+__global__ __launch_bounds__(256) void score_accum_kernel(Geom g, SeqTab tab, AllocIO aio,
+                                                          int n_alloc_blocks, const char* q,
+                                                          const char* k, const float2* partial,
+                                                          float* raw, int max_chunks,
+                                                          int rows_padded) {
+  using T = Tile<F32, D, RG>;
+  constexpr int kTileU4 = T::kKeys * T::kLdsRowU4 > 2048 ? T::kKeys * T::kLdsRowU4 : 2048;
+  __shared__ u32x4 ktile[kTileU4];
   __shared__ __align__(16) float rowc_s[kMaxRows];
+  __shared__ float2 pm[kMaxRows];
   __shared__ float colred[4][32];
 
+  if ((int)blockIdx.x < n_alloc_blocks) {
+    if (blockIdx.y == 0 && blockIdx.z == 0)
+      alloc_phase_b(aio, blockIdx.x, reinterpret_cast<char*>(ktile));
+    return;
+  }
   int seq, ch;
-  find_tile(tab, blockIdx.x, seq, ch);
+  find_tile(tab, blockIdx.x - n_alloc_blocks, seq, ch);
   const int kvh = blockIdx.y, layer = blockIdx.z;
   const int tok0 = tab.cu[seq], L = tab.cu[seq + 1] - tok0, P = L - g.window;
   const int hi = (seq * g.n_layers + layer) * g.n_kv_heads + kvh;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, hf = lane >> 5;
-  const int n_kt = 4 / g.row_groups, kt = wave % n_kt, rg = wave / n_kt;
-  const int keys_per_iter = 32 * n_kt;
+  constexpr int n_kt = T::kWaveCols;
+  const int kt = wave % n_kt, rg = wave / n_kt;
   const int blk0 = rg * g.blocks_per_group;
   int nb_count = g.row_blocks - blk0;
   nb_count = nb_count < 0 ? 0 : (nb_count > g.blocks_per_group ? g.blocks_per_group : nb_count);
   const float a = g.scale_log2e;
 
-  for (int r = threadIdx.x; r < kMaxRows; r += 256)
-    rowc_s[r] = r < rows_padded ? rowc[(int64_t)hi * rows_padded + r] : INFINITY;
+  const char* kbase = k + ((int64_t)layer * g.sl + (int64_t)kvh * g.sh + (int64_t)tok0 * g.st) * T::kEsize;
+  const int j_begin = ch * g.chunk_keys;
+  const int j_end = min(P, j_begin + g.chunk_keys);
+  const int64_t tok_bytes = g.st * T::kEsize;
+  const int ld_row0 = threadIdx.x / T::kRowU4, ld_col = threadIdx.x % T::kRowU4;
+  const int ld_lds = ld_row0 * T::kLdsRowU4 + ld_col;
+  const char* ld_base = kbase + ld_col * 16;
+  u32x4 pre[T::kLoads];
+  k_issue<F32, D, RG, T::kLoads>(pre, ld_base, tok_bytes, ld_row0, j_begin, L);
 
-  uint4 qreg[NBM][T::kHalfU4];
+  // Softmax constant of every window row: merge the (max, sum) pairs that pass A left per
+  // chunk of this head, c_r = max_r * a + log2(sum_r).  Each thread first folds a share of
+  // the chunks of one row (loads in batches of eight), LDS joins the shares.
+  {
+    const int n_chunks = (L + g.chunk_keys - 1) / g.chunk_keys;   // chunks pass A used
+    const int nparts = rows_padded >= 256 ? 1 : 256 / rows_padded;
+    const int cpp = (n_chunks + nparts - 1) / nparts;
+    const float2* hp = partial + (int64_t)hi * max_chunks * rows_padded;
+    for (int item = threadIdx.x; item < rows_padded * nparts; item += 256) {
+      const int r = item % rows_padded, part = item / rows_padded;
+      const int c_end = min(n_chunks, (part + 1) * cpp);
+      float mm = -INFINITY, zz = 0.f;
+      for (int c0 = part * cpp; c0 < c_end; c0 += 8) {
+        float2 st[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+          st[u] = c0 + u < c_end ? hp[(int64_t)(c0 + u) * rows_padded + r] : make_float2(-INFINITY, 0.f);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) merge_stats(mm, zz, st[u].x, st[u].y, a);
+      }
+      if (nparts == 1) rowc_s[r] = r < g.rows ? mm * a + log2f(zz) : INFINITY;
+      else pm[part * rows_padded + r] = make_float2(mm, zz);
+    }
+    if (nparts > 1) {
+      __syncthreads();
+      for (int r = threadIdx.x; r < rows_padded; r += 256) {
+        float mm = -INFINITY, zz = 0.f;
+        for (int part = 0; part < nparts; ++part) {
+          const float2 st = pm[part * rows_padded + r];
+          merge_stats(mm, zz, st.x, st.y, a);
+        }
+        // padded rows never contribute: +inf makes exp2(S*a - c) vanish
+        rowc_s[r] = r < g.rows ? mm * a + log2f(zz) : INFINITY;
+      }
+    }
+    for (int r = rows_padded + threadIdx.x; r < kMaxRows; r += 256) rowc_s[r] = INFINITY;
+  }
+
+  u32x4 qreg[NBM][T::kHalfU4];
   load_q<F32, D, NBM, T::kHalfU4>(qreg, g, q, layer, kvh, seq, blk0, nb_count, lane);
 
-  const char* kbase = k + ((int64_t)layer * g.sl + (int64_t)kvh * g.sh + (int64_t)tok0 * g.st) * T::kEsize;
-  const int64_t tok_bytes = g.st * T::kEsize;
   float* out = raw + ((int64_t)layer * g.n_kv_heads + kvh) * g.total_tokens + tok0;
-  const int j_begin = ch * kChunkKeys;
-  const int j_end = min(P, j_begin + kChunkKeys);
 
-  for (int j0 = j_begin; j0 < j_end; j0 += keys_per_iter) {
+  for (int j0 = j_begin; j0 < j_end; j0 += T::kKeys) {
     __syncthreads();
-    load_k_tile<F32, D>(ktile, kbase, tok_bytes, j0, keys_per_iter, L);
+    k_commit<F32, D, RG, T::kLoads>(pre, ktile, ld_lds);
     __syncthreads();
+    if (j0 + T::kKeys < j_end) k_issue<F32, D, RG, T::kLoads>(pre, ld_base, tok_bytes, ld_row0, j0 + T::kKeys, L);
     const int jw = j0 + 32 * kt;
     float col = 0.f;
     if (jw < j_end) {
-      uint4 kreg[T::kHalfU4];
-      const uint4* src = ktile + (32 * kt + (lane & 31)) * T::kLdsRowU4 + hf * T::kHalfU4;
+      u32x4 kreg[T::kHalfU4];
+      const u32x4* src = ktile + (32 * kt + (lane & 31)) * T::kLdsRowU4 + hf * T::kHalfU4;
 #pragma unroll
       for (int s = 0; s < T::kHalfU4; ++s) kreg[s] = src[s];
 #pragma unroll
@@ -272,19 +341,20 @@ __global__ __launch_bounds__(256) void score_accum_kernel(Geom g, SeqTab tab, co
       }
       col += __shfl_xor(col, 32);
     }
-    if (g.row_groups > 1) {
+    if (RG > 1) {
       // fixed-order sum over the row groups keeps the result deterministic
       if (lane < 32) colred[wave][lane] = col;
       __syncthreads();
       if (rg == 0) {
-        for (int t = 1; t < g.row_groups; ++t) col += colred[t * n_kt + kt][lane & 31];
+#pragma unroll
+        for (int t = 1; t < RG; ++t) col += colred[t * n_kt + kt][lane & 31];
       }
     }
     if (rg == 0 && lane < 32 && jw + lane < j_end) out[jw + lane] = col * g.inv_group;
   }
 }
 
-// ---- pooling + forced positions ----------------------------------------------------------
+// ---- pooling + forced positions (stand-alone scores) -------------------------------------
 __global__ __launch_bounds__(256) void pool_kernel(Geom g, SeqTab tab, const float* raw,
                                                    float* pooled) {
   int seq, tile;
@@ -303,41 +373,61 @@ __global__ __launch_bounds__(256) void pool_kernel(Geom g, SeqTab tab, const flo
   pooled[base + j] = s;
 }
 
-// ---- launcher ----------------------------------------------------------------------------
-template <bool F32, int D, int NBM>
-static int launch_score_t(const HostCfg& hc, const WsLayout& lay, const void* q, const void* k,
-                          float* pooled_out, char* ws, hipStream_t st) {
+// ---- launchers ---------------------------------------------------------------------------
+template <bool F32, int D, int NBM, int RG>
+static int launch_raw_t(const HostCfg& hc, const WsLayout& lay, const void* q, const void* k,
+                        const AllocIO* aio, char* ws, hipStream_t st) {
   const Geom& g = hc.g;
   float2* partial = reinterpret_cast<float2*>(ws + lay.partial);
-  float* rowc = reinterpret_cast<float*>(ws + lay.rowc);
   float* raw = reinterpret_cast<float*>(ws + lay.raw);
-  unsigned* cnt = reinterpret_cast<unsigned*>(ws + lay.stats_cnt);
-  const SeqTab tabA = tiles_for(hc.seq, kChunkKeys, 0);
-  const SeqTab tabB = tiles_for(hc.seq, kChunkKeys, g.window);
-  const SeqTab tabP = tiles_for(hc.seq, 256, 0);
-  dim3 gridA(tabA.tile0[tabA.n_seqs], g.n_kv_heads, g.n_layers);
-  dim3 gridB(tabB.tile0[tabB.n_seqs], g.n_kv_heads, g.n_layers);
-  dim3 gridP(tabP.tile0[tabP.n_seqs], g.n_kv_heads * g.n_layers, 1);
+  const SeqTab tabA = tiles_for(hc.seq, g.chunk_keys, 0);
+  const SeqTab tabB = tiles_for(hc.seq, g.chunk_keys, g.window);
+  AllocIO io;
+  memset(&io, 0, sizeof(io));
+  int n_alloc = 0;
+  if (aio) { io = *aio; n_alloc = aio->n_problems; }
+  dim3 gridA(tabA.tile0[tabA.n_seqs] + n_alloc, g.n_kv_heads, g.n_layers);
+  dim3 gridB(tabB.tile0[tabB.n_seqs] + n_alloc, g.n_kv_heads, g.n_layers);
   stage_mark(kStStats, st);
-  hipLaunchKernelGGL((score_stats_kernel<F32, D, NBM>), gridA, dim3(256), 0, st, g, tabA,
-                     (const char*)q, (const char*)k, partial, rowc, cnt, lay.max_chunks,
+  hipLaunchKernelGGL((score_stats_kernel<F32, D, NBM, RG>), gridA, dim3(256), 0, st, g, tabA, io,
+                     n_alloc, (const char*)q, (const char*)k, partial, lay.max_chunks,
                      lay.rows_padded);
   stage_mark(kStAccum, st);
-  hipLaunchKernelGGL((score_accum_kernel<F32, D, NBM>), gridB, dim3(256), 0, st, g, tabB,
-                     (const char*)q, (const char*)k, (const float*)rowc, raw, lay.rows_padded);
-  stage_mark(kStPool, st);
-  hipLaunchKernelGGL(pool_kernel, gridP, dim3(256), 0, st, g, tabP, (const float*)raw, pooled_out);
+  hipLaunchKernelGGL((score_accum_kernel<F32, D, NBM, RG>), gridB, dim3(256), 0, st, g, tabB, io,
+                     n_alloc, (const char*)q, (const char*)k, (const float2*)partial, raw,
+                     lay.max_chunks, lay.rows_padded);
   return check_launch();
 }
 
-int launch_score(const HostCfg& hc, const WsLayout& lay, const void* q, const void* k,
-                 float* pooled_out, char* ws, hipStream_t st) {
+template <bool F32, int D, int NBM>
+static int launch_raw_rg(const HostCfg& hc, const WsLayout& lay, const void* q, const void* k,
+                         const AllocIO* aio, char* ws, hipStream_t st) {
+  switch (hc.g.row_groups) {
+    case 1: return launch_raw_t<F32, D, NBM, 1>(hc, lay, q, k, aio, ws, st);
+    case 2: return launch_raw_t<F32, D, NBM, 2>(hc, lay, q, k, aio, ws, st);
+    case 4: return launch_raw_t<F32, D, NBM, 4>(hc, lay, q, k, aio, ws, st);
+  }
+  return LUKV_EINVAL;
+}
+
+int launch_score_raw(const HostCfg& hc, const WsLayout& lay, const void* q, const void* k,
+                     const AllocIO* aio, char* ws, hipStream_t st) {
   const Geom& g = hc.g;
-  if (!g.f32 && g.head_dim == 128) return launch_score_t<false, 128, 4>(hc, lay, q, k, pooled_out, ws, st);
-  if (!g.f32 && g.head_dim == 64) return launch_score_t<false, 64, 4>(hc, lay, q, k, pooled_out, ws, st);
-  if (g.f32 && g.head_dim == 64) return launch_score_t<true, 64, 4>(hc, lay, q, k, pooled_out, ws, st);
-  if (g.f32 && g.head_dim == 128) return launch_score_t<true, 128, 2>(hc, lay, q, k, pooled_out, ws, st);
+  if (!g.f32 && g.head_dim == 128) return launch_raw_rg<false, 128, 4>(hc, lay, q, k, aio, ws, st);
+  if (!g.f32 && g.head_dim == 64) return launch_raw_rg<false, 64, 4>(hc, lay, q, k, aio, ws, st);
+  if (g.f32 && g.head_dim == 64) return launch_raw_rg<true, 64, 4>(hc, lay, q, k, aio, ws, st);
+  if (g.f32 && g.head_dim == 128) return launch_raw_rg<true, 128, 2>(hc, lay, q, k, aio, ws, st);
   return LUKV_EDTYPE;
+}
+
+int launch_pool(const HostCfg& hc, const WsLayout& lay, float* pooled_out, char* ws, hipStream_t st) {
+  const Geom& g = hc.g;
+  const SeqTab tabP = tiles_for(hc.seq, 256, 0);
+  dim3 gridP(tabP.tile0[tabP.n_seqs], g.n_kv_heads * g.n_layers, 1);
+  stage_mark(kStPool, st);
+  hipLaunchKernelGGL(pool_kernel, gridP, dim3(256), 0, st, g, tabP,
+                     reinterpret_cast<const float*>(ws + lay.raw), pooled_out);
+  return check_launch();
 }
 
 }  // namespace lukv

@@ -34,8 +34,8 @@ LUKV_ST_CLAMPED = 2
 EXPORTS = ("lukv_workspace_bytes", "lukv_allocate_workspace_bytes", "lukv_score", "lukv_allocate",
            "lukv_select_compact", "lukv_evict", "lukv_set_stage_events", "lukv_stage_name",
            "lukv_strerror")
-LUKV_STAGE_END = 10
-LUKV_NUM_STAGE_EVENTS = 11
+LUKV_STAGE_END = 7
+LUKV_NUM_STAGE_EVENTS = 8
 
 
 class _CConfig(ctypes.Structure):
