@@ -121,20 +121,33 @@ def _slope(knots: Sequence[int], U: Sequence[float], a: int, b: int) -> float:
 
 
 def concave_hull(knots: Sequence[int], U: Sequence[float]) -> List[int]:
-    """Indices of the knots on the upper concave hull of (knots[g], U[g]).
+    """Indices of the knots that are vertices of the upper concave hull of (knots[g], U[g]).
 
     The profiled utility U(i) = L(0) - L(i) is the retained importance mass; the
     paper's convex non-increasing surrogate of the loss (PAVA on the marginal
     decreases) is the least concave majorant of U.  Between grid knots U is taken
-    linear, so the hull of the knots is the hull of the curve.  Collinear knots
-    merge (pop on <=), so hull slopes are strictly decreasing.
+    linear, so the hull of the knots is the hull of the curve.
+
+    Written as the definition of a strict vertex: knot g is on the hull iff every
+    chord from an earlier knot to g is strictly steeper than every chord from g to a
+    later knot (the two end knots always are).  Collinear knots are therefore not
+    vertices, and the slopes between consecutive vertices are strictly decreasing.
     """
-    st: List[int] = []
-    for g in range(len(knots)):
-        st.append(g)
-        while len(st) >= 3 and _slope(knots, U, st[-3], st[-2]) <= _slope(knots, U, st[-2], st[-1]):
-            del st[-2]
-    return st
+    G = len(knots)
+    n = np.asarray(knots, dtype=np.int64).astype(np.float64)
+    u = np.asarray(U, dtype=np.float32).astype(np.float64)
+    with np.errstate(divide="ignore", invalid="ignore"):
+        chord = (u[None, :] - u[:, None]) / (n[None, :] - n[:, None])   # chord[a, b], a < b used
+    hull = []
+    for g in range(G):
+        if g == 0 or g == G - 1:
+            hull.append(g)
+            continue
+        steepness_in = chord[:g, g].min()          # chords from earlier knots to g
+        steepness_out = chord[g, g + 1:].max()     # chords from g to later knots
+        if steepness_in > steepness_out:
+            hull.append(g)
+    return hull
 
 
 def marginal_gains(knots: Sequence[int], U: Sequence[float]) -> List[Tuple[int, int, float]]:

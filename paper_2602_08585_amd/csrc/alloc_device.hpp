@@ -9,9 +9,9 @@
 // find the gain g* at which the cumulated units (largest gain first) reach the remaining
 // budget, give every head all its units above g*, and hand the units at exactly g* out in
 // head order.
-//   phase A: one thread per head: monotone-chain upper hull of (knot, U) with the stack in
-//            LDS; hull segments clipped to (b_min, min(b_max, last knot)] with their gain as
-//            an order-preserving 64-bit key; per-problem sums for the feasibility check.
+//   phase A: one thread per (head, knot): hull vertices by the chord criterion; hull segments
+//            clipped to (b_min, min(b_max, last knot)] with their gain as an order-preserving
+//            64-bit key; per-problem sums for the feasibility check.
 //   phase B: weighted radix select (8 digits of 8 bits, LDS histogram of unit counts) for
 //            g*; budgets per head (ties by a prefix sum over heads).  The row offsets
 //            (prefix sum of all budgets) are written by whoever consumes the budgets next.
@@ -41,10 +41,9 @@ struct AllocIO {
   int64_t B[LUKV_MAX_SEQS];
 };
 
-struct HullEntry {
+struct HullPoint {
   int32_t n;
   float U;
-  double slope;  // gain of the segment ending at this knot
 };
 
 __device__ __forceinline__ unsigned long long gain_key(double x) {
@@ -77,18 +76,19 @@ __device__ __forceinline__ long long block_scan_i64(long long v, long long* sm, 
 }
 
 // Phase A for problem p.  lds: scratch of lds_bytes (>= 32 KiB), free for this call.
-// The batch's curves and knots are first copied to LDS with coalesced loads (a thread
-// walking its own curve in global memory would pay one memory latency per knot); the hull
-// stack then overwrites the copy in place (after knot g is read the stack holds at most g+1
-// entries, so it never overtakes the read position).
+// Hull vertices by their definition, one (head, knot) pair per thread: knot g is a vertex of
+// the upper concave hull iff every chord from an earlier knot to g is strictly steeper than
+// every chord from g to a later knot (end knots always are).  All chords are independent
+// fp64 divisions, so nothing here waits on a serial chain; consecutive vertices then give
+// the segments, whose gains are strictly decreasing by the same criterion.
 __device__ inline void alloc_phase_a(const AllocIO& io, int p, char* lds, int lds_bytes) {
   const int NH = io.n_heads, Gp = io.n_grid, t = threadIdx.x;
   const int64_t hbase = (int64_t)p * NH;
   long long* sm = reinterpret_cast<long long*>(lds);          // 4 slots
-  int* tops = reinterpret_cast<int*>(lds + 64);               // 256 stack heights
-  HullEntry* stacks = reinterpret_cast<HullEntry*>(lds + 64 + 1024);
-  int heads_per_batch = (lds_bytes - 64 - 1024) / (int)(sizeof(HullEntry) * Gp);
-  heads_per_batch = heads_per_batch > 256 ? 256 : heads_per_batch;
+  HullPoint* pts = reinterpret_cast<HullPoint*>(lds + 64);
+  int heads_per_batch = (lds_bytes - 64) / (int)((sizeof(HullPoint) + sizeof(int)) * Gp);
+  heads_per_batch = heads_per_batch > NH ? NH : heads_per_batch;
+  int* vertex = reinterpret_cast<int*>(lds + 64 + (int64_t)heads_per_batch * Gp * sizeof(HullPoint));
   long long sum_min = 0, sum_w = 0, bad = 0;
   if (heads_per_batch < 1) bad = 1;  // curve too long for the scratch: flagged, never run
   for (int h0 = 0; h0 < NH && heads_per_batch >= 1; h0 += heads_per_batch) {
@@ -96,47 +96,57 @@ __device__ inline void alloc_phase_a(const AllocIO& io, int p, char* lds, int ld
     const int64_t gbase = (hbase + h0) * Gp;
     __syncthreads();
     for (int i = t; i < nb * Gp; i += 256) {
-      HullEntry e;
+      HullPoint e;
       e.n = io.knots[gbase + i];
       e.U = io.curves[gbase + i];
-      e.slope = 0.0;
-      stacks[i] = e;
+      pts[i] = e;
     }
     __syncthreads();
-    if (t < nb) {
-      HullEntry* st = stacks + (int64_t)t * Gp;
-      int top = 0;
-      for (int g = 0; g < Gp; ++g) {
-        HullEntry e = st[g];
-        // pop while the segment below is not steeper than the one to the new knot
-        while (top >= 1) {
-          const HullEntry b = st[top - 1];
-          e.slope = ((double)e.U - (double)b.U) / (double)(e.n - b.n);
-          if (top >= 2 && b.slope <= e.slope) --top; else break;
-        }
-        st[top++] = e;
-      }
-      tops[t] = top;
-      const long long lo_b = io.b_min[hbase + h0 + t];
-      const long long cap = min((long long)io.b_max[hbase + h0 + t], (long long)st[top - 1].n);
-      if (lo_b < 0 || lo_b > cap) bad = 1;
-      sum_min += lo_b;
-    }
-    __syncthreads();
-    // hull segments of the whole batch, clipped to (b_min, cap], stored coalesced
     for (int i = t; i < nb * Gp; i += 256) {
-      const int hh = i / Gp, e = i - hh * Gp;
-      const HullEntry* sh = stacks + (int64_t)hh * Gp;
-      const int tp = tops[hh];
+      const int hh = i / Gp, g = i - hh * Gp;
+      const HullPoint* ph = pts + hh * Gp;
+      const HullPoint me = ph[g];
+      int is_vertex = 1;
+      if (g > 0 && g < Gp - 1) {
+        double steep_in = INFINITY, steep_out = -INFINITY;
+        // independent divisions: unrolled so that several are in flight (one fp64 division
+        // is a long dependent chain of its own)
+#pragma unroll 8
+        for (int a = 0; a < g; ++a) {
+          const HullPoint o = ph[a];
+          const double s = ((double)me.U - (double)o.U) / (double)(me.n - o.n);
+          steep_in = s < steep_in ? s : steep_in;
+        }
+#pragma unroll 8
+        for (int c = g + 1; c < Gp; ++c) {
+          const HullPoint o = ph[c];
+          const double s = ((double)o.U - (double)me.U) / (double)(o.n - me.n);
+          steep_out = s > steep_out ? s : steep_out;
+        }
+        is_vertex = steep_in > steep_out;
+      }
+      vertex[i] = is_vertex;
+    }
+    __syncthreads();
+    // one segment per vertex (to the next vertex), clipped to (b_min, cap], stored coalesced
+    for (int i = t; i < nb * Gp; i += 256) {
+      const int hh = i / Gp, g = i - hh * Gp;
+      const HullPoint* ph = pts + hh * Gp;
+      const long long lb = io.b_min[hbase + h0 + hh];
+      const long long cp = min((long long)io.b_max[hbase + h0 + hh], (long long)ph[Gp - 1].n);
+      if (g == 0) {
+        if (lb < 0 || lb > cp) bad = 1;
+        sum_min += lb;
+      }
       unsigned w = 0;
       unsigned long long key = 0;
-      if (e + 1 < tp) {
-        const long long lb = io.b_min[hbase + h0 + hh];
-        const long long cp = min((long long)io.b_max[hbase + h0 + hh], (long long)sh[tp - 1].n);
-        const HullEntry a = sh[e], b = sh[e + 1];
+      if (vertex[i] && g < Gp - 1) {
+        int c = g + 1;
+        while (!vertex[hh * Gp + c]) ++c;   // the last knot is always a vertex
+        const HullPoint a = ph[g], b = ph[c];
         const long long lo = max((long long)a.n, lb), hi = min((long long)b.n, cp);
         w = hi > lo ? (unsigned)(hi - lo) : 0u;
-        key = gain_key(b.slope);
+        key = gain_key(((double)b.U - (double)a.U) / (double)(b.n - a.n));
       }
       io.seg_key[gbase + i] = key;
       io.seg_w[gbase + i] = w;
@@ -154,13 +164,15 @@ __device__ inline void alloc_phase_a(const AllocIO& io, int p, char* lds, int ld
   }
 }
 
-// Phase B for problem p (after phase A's global writes are visible).  lds >= 4 KiB.
-__device__ inline void alloc_phase_b(const AllocIO& io, int p, char* lds) {
+// Phase B for problem p (after phase A's global writes are visible).  lds: scratch of
+// lds_bytes (>= 8 KiB); when the problem's segments fit they are staged there once.
+__device__ inline void alloc_phase_b(const AllocIO& io, int p, char* lds, int lds_bytes) {
   const int NH = io.n_heads, Gp = io.n_grid, t = threadIdx.x;
+  const int lane = t & 63, wave = t >> 6;
   const int64_t hbase = (int64_t)p * NH;
   const int64_t nseg = (int64_t)NH * Gp;
-  long long* sm = reinterpret_cast<long long*>(lds);                       // 4 slots
-  unsigned long long* sel = reinterpret_cast<unsigned long long*>(lds + 64);  // prefix, rem
+  long long* sm = reinterpret_cast<long long*>(lds);                          // 4 slots
+  unsigned long long* sel = reinterpret_cast<unsigned long long*>(lds + 64);  // prefix, rem, and, or
   unsigned long long* hist = reinterpret_cast<unsigned long long*>(lds + 128);  // 256 bins
   const unsigned long long* skey = io.seg_key + hbase * Gp;
   const unsigned* sw = io.seg_w + hbase * Gp;
@@ -170,12 +182,42 @@ __device__ inline void alloc_phase_b(const AllocIO& io, int p, char* lds) {
   const bool infeasible = tot_bad != 0 || R < 0 || R > tot_w;
   const bool active = !infeasible && R > 0;
 
+  // stage the segments in LDS when they fit (every later pass re-reads them)
+  const int64_t cap = (lds_bytes - 4096) / 12;
+  __syncthreads();
+  if (nseg <= cap) {
+    unsigned long long* lk = reinterpret_cast<unsigned long long*>(lds + 4096);
+    unsigned* lw = reinterpret_cast<unsigned*>(lds + 4096 + nseg * 8);
+    for (int64_t i = t; i < nseg; i += 256) { lk[i] = skey[i]; lw[i] = sw[i]; }
+    skey = lk;
+    sw = lw;
+  }
+  if (t == 0) { sel[0] = 0ull; sel[1] = (unsigned long long)R; sel[2] = ~0ull; sel[3] = 0ull; }
+  __syncthreads();
+
   // weighted radix select of the threshold gain g*: W(> g*) < R <= W(>= g*)
-  __syncthreads();
-  if (t == 0) { sel[0] = 0ull; sel[1] = (unsigned long long)R; }
-  __syncthreads();
   if (active) {
+    // digits on which all live keys agree need no histogram
+    unsigned long long k_and = ~0ull, k_or = 0ull;
+    for (int64_t i = t; i < nseg; i += 256)
+      if (sw[i]) { const unsigned long long key = skey[i]; k_and &= key; k_or |= key; }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      k_and &= ((unsigned long long)(unsigned)__shfl_xor((int)(k_and >> 32), o) << 32) | (unsigned)__shfl_xor((int)k_and, o);
+      k_or |= ((unsigned long long)(unsigned)__shfl_xor((int)(k_or >> 32), o) << 32) | (unsigned)__shfl_xor((int)k_or, o);
+    }
+    if (lane == 0) { atomicAnd(&sel[2], k_and); atomicOr(&sel[3], k_or); }
+    __syncthreads();
+    const unsigned long long differ = sel[2] ^ sel[3];
+    const unsigned long long common = sel[2];
     for (int shift = 56; shift >= 0; shift -= 8) {
+      if (((differ >> shift) & 255ull) == 0ull) {
+        // uniform: same digit for every live key, the wanted rank is unchanged
+        __syncthreads();
+        if (t == 0) sel[0] |= ((common >> shift) & 255ull) << shift;
+        __syncthreads();
+        continue;
+      }
       hist[t] = 0ull;
       __syncthreads();
       const unsigned long long prefix = sel[0];
@@ -188,14 +230,27 @@ __device__ inline void alloc_phase_b(const AllocIO& io, int p, char* lds) {
         }
       }
       __syncthreads();
-      const long long mine = (long long)hist[255 - t];  // thread t owns descending bin t
-      long long dummy;
-      const long long before = block_scan_i64(mine, sm, &dummy);
-      const long long want = (long long)sel[1];
-      __syncthreads();
-      if (before < want && want <= before + mine) {
-        sel[0] = prefix | ((unsigned long long)(255 - t) << shift);
-        sel[1] = (unsigned long long)(want - before);
+      if (wave == 0) {
+        // lane l owns the descending bins 4l .. 4l+3 (bin index 255-4l-k)
+        long long v[4], s4 = 0;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) { v[k] = (long long)hist[255 - 4 * lane - k]; s4 += v[k]; }
+        long long incl = s4;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+          const long long up = shfl_up_i64(incl, o);
+          if (lane >= o) incl += up;
+        }
+        long long before = incl - s4;
+        const long long want = (long long)sel[1];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          if (before < want && want <= before + v[k]) {
+            sel[0] = prefix | ((unsigned long long)(255 - 4 * lane - k) << shift);
+            sel[1] = (unsigned long long)(want - before);
+          }
+          before += v[k];
+        }
       }
       __syncthreads();
     }

@@ -8,7 +8,7 @@ __global__ __launch_bounds__(256) void allocate_kernel(AllocIO io) {
   __shared__ __align__(16) char lds[32768];
   alloc_phase_a(io, blockIdx.x, lds, (int)sizeof(lds));
   __syncthreads();
-  alloc_phase_b(io, blockIdx.x, lds);
+  alloc_phase_b(io, blockIdx.x, lds, (int)sizeof(lds));
 }
 
 // offsets = exclusive prefix sum of all budgets (stand-alone call; one workgroup)

@@ -127,8 +127,12 @@ __global__ __launch_bounds__(256) void score_stats_kernel(Geom g, SeqTab tab, Al
   __shared__ float2 wstat[4][NBM][32];
 
   if ((int)blockIdx.x < n_alloc_blocks) {
-    if (blockIdx.y == 0 && blockIdx.z == 0)
+    if (blockIdx.y == 0 && blockIdx.z == 0) {
+      // a short latency-bound job sharing its CU with throughput-bound scoring waves:
+      // let it issue whenever it is ready so that it finishes well inside this launch
+      __builtin_amdgcn_s_setprio(3);
       alloc_phase_a(aio, blockIdx.x, reinterpret_cast<char*>(ktile), (int)sizeof(ktile));
+    }
     return;
   }
   int seq, ch;
@@ -242,8 +246,10 @@ __global__ __launch_bounds__(256) void score_accum_kernel(Geom g, SeqTab tab, Al
   __shared__ float colred[4][32];
 
   if ((int)blockIdx.x < n_alloc_blocks) {
-    if (blockIdx.y == 0 && blockIdx.z == 0)
-      alloc_phase_b(aio, blockIdx.x, reinterpret_cast<char*>(ktile));
+    if (blockIdx.y == 0 && blockIdx.z == 0) {
+      __builtin_amdgcn_s_setprio(3);
+      alloc_phase_b(aio, blockIdx.x, reinterpret_cast<char*>(ktile), (int)sizeof(ktile));
+    }
     return;
   }
   int seq, ch;

@@ -60,6 +60,33 @@ def test_infeasible_budgets_flagged():
     assert st == 1 and b.tolist() == [3, 3]
 
 
+# --- monotone chain (textbook upper-hull scan) as a second construction of the same hull ---
+
+def _monotone_chain(knots, U):
+    st = []
+    for g in range(len(knots)):
+        st.append(g)
+        while len(st) >= 3 and O._slope(knots, U, st[-3], st[-2]) <= O._slope(knots, U, st[-2], st[-1]):
+            del st[-2]
+    return st
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_vertex_definition_equals_monotone_chain(seed):
+    rng = np.random.default_rng(700 + seed)
+    Gp = int(rng.integers(2, 40))
+    L = int(rng.integers(Gp, 4000))
+    if seed % 2:
+        inc = rng.integers(0, 4, size=Gp).astype(np.float32) / 8     # many collinear runs
+    else:
+        z = rng.standard_normal(Gp)
+        inc = (0.5 * z * z).astype(np.float32)
+    inc[0] = 0
+    U = np.cumsum(inc).astype(np.float32)
+    knots = ((np.arange(Gp) * L) // (Gp - 1)).astype(np.int32) if Gp > 1 else np.zeros(1, np.int32)
+    assert O.concave_hull(knots, U) == _monotone_chain(knots, U)
+
+
 # --- unit-level PAVA (textbook pool-adjacent-violators on the marginal decreases) ----------
 
 def _pava_nonincreasing(d):
