@@ -1,7 +1,7 @@
 // Device code of step 2, the global head-level budget allocation (Sec. 4.2 "Efficient
 // Optimization via Convex Hull Relaxation", Eq. 8-10; App. A.2 "Optimality of greedy
-// allocation"), written for a 256-thread workgroup per problem so that it can run either
-// in its own kernel or as one extra workgroup of a score kernel.
+// allocation"), written so that it can run in its own kernel or as a few extra workgroups
+// of other kernels of the path (it never looks at scores).
 //
 // The unit-by-unit greedy of the paper picks, B times, the head whose next unit has the
 // largest marginal gain.  Gains are constant along a hull segment and strictly decreasing
@@ -9,12 +9,16 @@
 // find the gain g* at which the cumulated units (largest gain first) reach the remaining
 // budget, give every head all its units above g*, and hand the units at exactly g* out in
 // head order.
-//   phase A: one thread per (head, knot): hull vertices by the chord criterion; hull segments
-//            clipped to (b_min, min(b_max, last knot)] with their gain as an order-preserving
-//            64-bit key; per-problem sums for the feasibility check.
-//   phase B: weighted radix select (8 digits of 8 bits, LDS histogram of unit counts) for
-//            g*; budgets per head (ties by a prefix sum over heads).  The row offsets
-//            (prefix sum of all budgets) are written by whoever consumes the budgets next.
+//   phase A: hull vertices by their definition, four threads per (head, knot): knot g is a
+//            vertex of the upper concave hull iff every chord from an earlier knot to g is
+//            strictly steeper than every chord from g to a later knot (end knots always
+//            are).  All chords are independent fp64 divisions: no serial chain, any number
+//            of workgroups.
+//   phase B: one workgroup per problem: a segment per vertex (to the next vertex), clipped to
+//            (b_min, min(b_max, last knot)], gain as an order-preserving 64-bit key; weighted
+//            radix select (8 digits of 8 bits) for g*; budgets per head, ties by a prefix
+//            sum over heads.  The row offsets (prefix sum of all budgets) are written by
+//            whoever consumes the budgets next.
 //
 // Nothing here may be fused: a gain is one fp64 subtract and one fp64 divide, so that it
 // compares bit for bit like the same expression evaluated on a CPU.
@@ -35,16 +39,17 @@ struct AllocIO {
   int32_t* budgets;
   int64_t* offsets;
   int32_t* status;
-  unsigned long long* seg_key;  // [n_problems * n_heads * n_grid]
+  int32_t* vertex;              // [n_problems * n_heads * n_grid] hull-vertex flags (phase A -> B)
+  unsigned long long* seg_key;  // same shape; used when a problem's segments do not fit in LDS
   unsigned* seg_w;              // same
-  long long* meta;              // [n_problems * 4]: sum b_min, sum units, bad flag
   int64_t B[LUKV_MAX_SEQS];
 };
 
-struct HullPoint {
-  int32_t n;
-  float U;
-};
+constexpr int kAllocPartsPerKnot = 4;   // threads sharing the chords of one knot in phase A
+
+__host__ __device__ inline int alloc_blocks_a(int n_heads, int n_grid) {
+  return (n_heads * n_grid * kAllocPartsPerKnot + 255) / 256;   // 256-thread blocks per problem
+}
 
 __device__ __forceinline__ unsigned long long gain_key(double x) {
   unsigned long long u = (unsigned long long)__double_as_longlong(x);
@@ -57,9 +62,25 @@ __device__ __forceinline__ long long shfl_up_i64(long long v, int o) {
   return ((long long)hi << 32) | (unsigned)lo;
 }
 
-// Exclusive scan of one int64 per thread over 256 threads (4 waves); sm has >= 4 slots.
+__device__ __forceinline__ long long shfl_xor_i64(long long v, int o) {
+  int lo = __shfl_xor((int)(v & 0xFFFFFFFFll), o), hi = __shfl_xor((int)(v >> 32), o);
+  return ((long long)hi << 32) | (unsigned)lo;
+}
+
+__device__ __forceinline__ long long shfl_i64(long long v, int src) {
+  int lo = __shfl((int)(v & 0xFFFFFFFFll), src), hi = __shfl((int)(v >> 32), src);
+  return ((long long)hi << 32) | (unsigned)lo;
+}
+
+__device__ __forceinline__ double shfl_xor_f64(double v, int o) {
+  const long long b = __double_as_longlong(v);
+  const int lo = __shfl_xor((int)(b & 0xFFFFFFFFll), o), hi = __shfl_xor((int)(b >> 32), o);
+  return __longlong_as_double(((long long)hi << 32) | (unsigned)lo);
+}
+
+// Exclusive scan of one int64 per thread over the workgroup (<= 16 waves); sm has 16 slots.
 __device__ __forceinline__ long long block_scan_i64(long long v, long long* sm, long long* total) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n_waves = blockDim.x >> 6;
   long long incl = v;
 #pragma unroll
   for (int o = 1; o < 64; o <<= 1) {
@@ -69,206 +90,253 @@ __device__ __forceinline__ long long block_scan_i64(long long v, long long* sm, 
   __syncthreads();
   if (lane == 63) sm[wave] = incl;
   __syncthreads();
-  long long before = 0;
-  for (int w = 0; w < wave; ++w) before += sm[w];
-  *total = sm[0] + sm[1] + sm[2] + sm[3];
+  long long before = 0, tot = 0;
+  for (int w = 0; w < n_waves; ++w) {
+    if (w < wave) before += sm[w];
+    tot += sm[w];
+  }
+  *total = tot;
   return before + incl - v;
 }
 
-// Phase A for problem p.  lds: scratch of lds_bytes (>= 32 KiB), free for this call.
-// Hull vertices by their definition, one (head, knot) pair per thread: knot g is a vertex of
-// the upper concave hull iff every chord from an earlier knot to g is strictly steeper than
-// every chord from g to a later knot (end knots always are).  All chords are independent
-// fp64 divisions, so nothing here waits on a serial chain; consecutive vertices then give
-// the segments, whose gains are strictly decreasing by the same criterion.
-__device__ inline void alloc_phase_a(const AllocIO& io, int p, char* lds, int lds_bytes) {
-  const int NH = io.n_heads, Gp = io.n_grid, t = threadIdx.x;
-  const int64_t hbase = (int64_t)p * NH;
-  long long* sm = reinterpret_cast<long long*>(lds);          // 4 slots
-  HullPoint* pts = reinterpret_cast<HullPoint*>(lds + 64);
-  int heads_per_batch = (lds_bytes - 64) / (int)((sizeof(HullPoint) + sizeof(int)) * Gp);
-  heads_per_batch = heads_per_batch > NH ? NH : heads_per_batch;
-  int* vertex = reinterpret_cast<int*>(lds + 64 + (int64_t)heads_per_batch * Gp * sizeof(HullPoint));
-  long long sum_min = 0, sum_w = 0, bad = 0;
-  if (heads_per_batch < 1) bad = 1;  // curve too long for the scratch: flagged, never run
-  for (int h0 = 0; h0 < NH && heads_per_batch >= 1; h0 += heads_per_batch) {
-    const int nb = min(heads_per_batch, NH - h0);
-    const int64_t gbase = (hbase + h0) * Gp;
-    __syncthreads();
-    for (int i = t; i < nb * Gp; i += 256) {
-      HullPoint e;
-      e.n = io.knots[gbase + i];
-      e.U = io.curves[gbase + i];
-      pts[i] = e;
+// Phase A: 256-thread block `blk` (0 .. alloc_blocks_a-1) of problem p.
+__device__ inline void alloc_phase_a(const AllocIO& io, int p, int blk) {
+  const int NH = io.n_heads, Gp = io.n_grid;
+  const int unit = blk * 256 + threadIdx.x;
+  const int item = unit / kAllocPartsPerKnot, part = unit % kAllocPartsPerKnot;
+  const bool live = item < NH * Gp;
+  const int h = live ? item / Gp : 0, g = live ? item - h * Gp : 0;
+  const int64_t base = ((int64_t)p * NH + h) * Gp;
+  const int32_t* n = io.knots + base;
+  const float* U = io.curves + base;
+  const int n_me = n[g];
+  const double u_me = (double)U[g];
+  double steep_in = INFINITY, steep_out = -INFINITY;
+  if (live && g > 0 && g < Gp - 1) {
+    // independent divisions, unrolled so that several are in flight
+#pragma unroll 4
+    for (int a = part; a < g; a += kAllocPartsPerKnot) {
+      const double s = (u_me - (double)U[a]) / (double)(n_me - n[a]);
+      steep_in = s < steep_in ? s : steep_in;
     }
-    __syncthreads();
-    for (int i = t; i < nb * Gp; i += 256) {
-      const int hh = i / Gp, g = i - hh * Gp;
-      const HullPoint* ph = pts + hh * Gp;
-      const HullPoint me = ph[g];
-      int is_vertex = 1;
-      if (g > 0 && g < Gp - 1) {
-        double steep_in = INFINITY, steep_out = -INFINITY;
-        // independent divisions: unrolled so that several are in flight (one fp64 division
-        // is a long dependent chain of its own)
-#pragma unroll 8
-        for (int a = 0; a < g; ++a) {
-          const HullPoint o = ph[a];
-          const double s = ((double)me.U - (double)o.U) / (double)(me.n - o.n);
-          steep_in = s < steep_in ? s : steep_in;
-        }
-#pragma unroll 8
-        for (int c = g + 1; c < Gp; ++c) {
-          const HullPoint o = ph[c];
-          const double s = ((double)o.U - (double)me.U) / (double)(o.n - me.n);
-          steep_out = s > steep_out ? s : steep_out;
-        }
-        is_vertex = steep_in > steep_out;
-      }
-      vertex[i] = is_vertex;
-    }
-    __syncthreads();
-    // one segment per vertex (to the next vertex), clipped to (b_min, cap], stored coalesced
-    for (int i = t; i < nb * Gp; i += 256) {
-      const int hh = i / Gp, g = i - hh * Gp;
-      const HullPoint* ph = pts + hh * Gp;
-      const long long lb = io.b_min[hbase + h0 + hh];
-      const long long cp = min((long long)io.b_max[hbase + h0 + hh], (long long)ph[Gp - 1].n);
-      if (g == 0) {
-        if (lb < 0 || lb > cp) bad = 1;
-        sum_min += lb;
-      }
-      unsigned w = 0;
-      unsigned long long key = 0;
-      if (vertex[i] && g < Gp - 1) {
-        int c = g + 1;
-        while (!vertex[hh * Gp + c]) ++c;   // the last knot is always a vertex
-        const HullPoint a = ph[g], b = ph[c];
-        const long long lo = max((long long)a.n, lb), hi = min((long long)b.n, cp);
-        w = hi > lo ? (unsigned)(hi - lo) : 0u;
-        key = gain_key(((double)b.U - (double)a.U) / (double)(b.n - a.n));
-      }
-      io.seg_key[gbase + i] = key;
-      io.seg_w[gbase + i] = w;
-      sum_w += w;
+#pragma unroll 4
+    for (int c = g + 1 + part; c < Gp; c += kAllocPartsPerKnot) {
+      const double s = ((double)U[c] - u_me) / (double)(n[c] - n_me);
+      steep_out = s > steep_out ? s : steep_out;
     }
   }
-  long long tot_min, tot_w, tot_bad;
-  block_scan_i64(sum_min, sm, &tot_min);
-  block_scan_i64(sum_w, sm, &tot_w);
-  block_scan_i64(bad, sm, &tot_bad);
-  if (t == 0) {
-    io.meta[p * 4 + 0] = tot_min;
-    io.meta[p * 4 + 1] = tot_w;
-    io.meta[p * 4 + 2] = tot_bad;
+#pragma unroll
+  for (int o = 1; o < kAllocPartsPerKnot; o <<= 1) {
+    const double i2 = shfl_xor_f64(steep_in, o), o2 = shfl_xor_f64(steep_out, o);
+    steep_in = i2 < steep_in ? i2 : steep_in;
+    steep_out = o2 > steep_out ? o2 : steep_out;
   }
+  if (live && part == 0) io.vertex[base + g] = (g == 0 || g == Gp - 1) ? 1 : (steep_in > steep_out ? 1 : 0);
 }
 
-// Phase B for problem p (after phase A's global writes are visible).  lds: scratch of
-// lds_bytes (>= 8 KiB); when the problem's segments fit they are staged there once.
+// Phase B for problem p (after phase A's flags are visible).  Any workgroup size that is a
+// multiple of 64 from 256 to 1024; lds: scratch of lds_bytes (>= 32 KiB), free for this call.
+// Everything a thread walks more than once (vertex flags, knots, curves, segments, per-head
+// sums) is staged in LDS when the problem fits (up to 1024 segments and 1024 heads; larger
+// problems use the workspace and global memory, slower but the same arithmetic).  The radix
+// select itself is wave-synchronous on wave 0, its segments held in registers, so a small
+// problem pays no workgroup barrier per digit.
 __device__ inline void alloc_phase_b(const AllocIO& io, int p, char* lds, int lds_bytes) {
-  const int NH = io.n_heads, Gp = io.n_grid, t = threadIdx.x;
+  constexpr int kRegSegs = 16;              // segments per lane that wave 0 keeps in registers
+  const int NH = io.n_heads, Gp = io.n_grid, t = threadIdx.x, nt = blockDim.x;
   const int lane = t & 63, wave = t >> 6;
   const int64_t hbase = (int64_t)p * NH;
   const int64_t nseg = (int64_t)NH * Gp;
-  long long* sm = reinterpret_cast<long long*>(lds);                          // 4 slots
-  unsigned long long* sel = reinterpret_cast<unsigned long long*>(lds + 64);  // prefix, rem, and, or
-  unsigned long long* hist = reinterpret_cast<unsigned long long*>(lds + 128);  // 256 bins
-  const unsigned long long* skey = io.seg_key + hbase * Gp;
-  const unsigned* sw = io.seg_w + hbase * Gp;
+  long long* sm = reinterpret_cast<long long*>(lds);                            // 16 slots
+  long long* red = reinterpret_cast<long long*>(lds + 128);                     // sum b_min, sum w, bad
+  unsigned long long* sel = reinterpret_cast<unsigned long long*>(lds + 160);   // g*, ties, and, or
+  unsigned long long* hist = reinterpret_cast<unsigned long long*>(lds + 192);  // 256 bins of units
+  unsigned* hcnt = reinterpret_cast<unsigned*>(lds + 192 + 2048);               // 256 bins of segments
+  const int32_t* vtx = io.vertex + hbase * Gp;
+  const int32_t* kn = io.knots + hbase * Gp;
+  const float* cu = io.curves + hbase * Gp;
 
-  const long long tot_min = io.meta[p * 4 + 0], tot_w = io.meta[p * 4 + 1], tot_bad = io.meta[p * 4 + 2];
-  const long long R = io.B[p] - tot_min;
-  const bool infeasible = tot_bad != 0 || R < 0 || R > tot_w;
+  // LDS plan (small problems): flags/knots/curves [nseg] + segment key/weight [nseg] + per-head
+  // gt/eq sums [NH]
+  const bool small = nseg <= 1024 && NH <= 1024 && lds_bytes >= 4096 + 1024 * 24 + 1024 * 4;
+  int32_t* l_kn = reinterpret_cast<int32_t*>(lds + 4096);
+  float* l_cu = reinterpret_cast<float*>(lds + 4096 + nseg * 4);
+  unsigned* l_w = reinterpret_cast<unsigned*>(lds + 4096 + nseg * 8);
+  unsigned long long* l_key = reinterpret_cast<unsigned long long*>(lds + 4096 + (nseg * 12 + 7) / 8 * 8);
+  unsigned* l_vtx = reinterpret_cast<unsigned*>(lds + 4096 + (nseg * 12 + 7) / 8 * 8 + nseg * 8);
+  unsigned long long* skey = small ? l_key : io.seg_key + hbase * Gp;
+  unsigned* sw = small ? l_w : io.seg_w + hbase * Gp;
+  __syncthreads();
+  if (t == 0) {
+    red[0] = red[1] = red[2] = 0;
+    sel[0] = 0ull; sel[1] = 0ull; sel[2] = ~0ull; sel[3] = 0ull;
+  }
+  if (small)
+    for (int i = t; i < (int)nseg; i += nt) { l_vtx[i] = (unsigned)vtx[i]; l_kn[i] = kn[i]; l_cu[i] = cu[i]; }
+  __syncthreads();
+
+  // one segment per vertex (to the next vertex), clipped to (b_min, cap]
+  long long sum_min = 0, sum_w = 0, bad = 0;
+  unsigned long long k_and = ~0ull, k_or = 0ull;
+  for (int64_t i = t; i < nseg; i += nt) {
+    const int h = (int)(i / Gp), g = (int)(i - (int64_t)h * Gp);
+    const int64_t hb = (int64_t)h * Gp;
+    const long long lb = io.b_min[hbase + h];
+    const long long cp = min((long long)io.b_max[hbase + h], (long long)(small ? l_kn[hb + Gp - 1] : kn[hb + Gp - 1]));
+    if (g == 0) {
+      if (lb < 0 || lb > cp) bad = 1;
+      sum_min += lb;
+    }
+    unsigned w = 0;
+    unsigned long long key = 0;
+    if (g < Gp - 1 && (small ? l_vtx[i] != 0u : vtx[i] != 0)) {
+      int c = g + 1;   // next vertex; the last knot is always one
+      if (small) { while (c < Gp - 1 && !l_vtx[hb + c]) ++c; }
+      else { while (c < Gp - 1 && !vtx[hb + c]) ++c; }
+      const long long na = small ? l_kn[i] : kn[i], nb = small ? l_kn[hb + c] : kn[hb + c];
+      const double ua = (double)(small ? l_cu[i] : cu[i]), ub = (double)(small ? l_cu[hb + c] : cu[hb + c]);
+      const long long lo = max(na, lb), hi = min(nb, cp);
+      w = hi > lo ? (unsigned)(hi - lo) : 0u;
+      key = gain_key((ub - ua) / (double)(nb - na));
+    }
+    skey[i] = key;
+    sw[i] = w;
+    sum_w += w;
+    if (w) { k_and &= key; k_or |= key; }
+  }
+  // workgroup sums: most threads hold nothing, so only the others touch the LDS counters
+  if (sum_min) atomicAdd(reinterpret_cast<unsigned long long*>(&red[0]), (unsigned long long)sum_min);
+  if (sum_w) {
+    atomicAdd(reinterpret_cast<unsigned long long*>(&red[1]), (unsigned long long)sum_w);
+    atomicAnd(&sel[2], k_and);
+    atomicOr(&sel[3], k_or);
+  }
+  if (bad) atomicAdd(reinterpret_cast<unsigned long long*>(&red[2]), 1ull);
+  __syncthreads();
+  const long long R = io.B[p] - red[0];
+  const bool infeasible = red[2] != 0 || R < 0 || R > red[1];
   const bool active = !infeasible && R > 0;
 
-  // stage the segments in LDS when they fit (every later pass re-reads them)
-  const int64_t cap = (lds_bytes - 4096) / 12;
-  __syncthreads();
-  if (nseg <= cap) {
-    unsigned long long* lk = reinterpret_cast<unsigned long long*>(lds + 4096);
-    unsigned* lw = reinterpret_cast<unsigned*>(lds + 4096 + nseg * 8);
-    for (int64_t i = t; i < nseg; i += 256) { lk[i] = skey[i]; lw[i] = sw[i]; }
-    skey = lk;
-    sw = lw;
-  }
-  if (t == 0) { sel[0] = 0ull; sel[1] = (unsigned long long)R; sel[2] = ~0ull; sel[3] = 0ull; }
-  __syncthreads();
-
-  // weighted radix select of the threshold gain g*: W(> g*) < R <= W(>= g*)
-  if (active) {
-    // digits on which all live keys agree need no histogram
-    unsigned long long k_and = ~0ull, k_or = 0ull;
-    for (int64_t i = t; i < nseg; i += 256)
-      if (sw[i]) { const unsigned long long key = skey[i]; k_and &= key; k_or |= key; }
+  // weighted radix select of the threshold gain g*: W(> g*) < R <= W(>= g*), on wave 0
+  if (active && wave == 0) {
+    const unsigned long long differ = sel[2] ^ sel[3], common = sel[2];
+    const bool in_regs = nseg <= 64 * kRegSegs;
+    unsigned long long rkey[kRegSegs];
+    unsigned rw[kRegSegs];
+    if (in_regs) {
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-      k_and &= ((unsigned long long)(unsigned)__shfl_xor((int)(k_and >> 32), o) << 32) | (unsigned)__shfl_xor((int)k_and, o);
-      k_or |= ((unsigned long long)(unsigned)__shfl_xor((int)(k_or >> 32), o) << 32) | (unsigned)__shfl_xor((int)k_or, o);
+      for (int u = 0; u < kRegSegs; ++u) {
+        const int64_t i = lane + 64 * u;
+        rw[u] = i < nseg ? sw[i] : 0u;
+        rkey[u] = i < nseg ? skey[i] : 0ull;
+      }
     }
-    if (lane == 0) { atomicAnd(&sel[2], k_and); atomicOr(&sel[3], k_or); }
-    __syncthreads();
-    const unsigned long long differ = sel[2] ^ sel[3];
-    const unsigned long long common = sel[2];
+    unsigned long long prefix = 0ull;
+    long long want = R;
     for (int shift = 56; shift >= 0; shift -= 8) {
       if (((differ >> shift) & 255ull) == 0ull) {
-        // uniform: same digit for every live key, the wanted rank is unchanged
-        __syncthreads();
-        if (t == 0) sel[0] |= ((common >> shift) & 255ull) << shift;
-        __syncthreads();
+        prefix |= ((common >> shift) & 255ull) << shift;   // every live key has this digit
         continue;
       }
-      hist[t] = 0ull;
-      __syncthreads();
-      const unsigned long long prefix = sel[0];
-      for (int64_t i = t; i < nseg; i += 256) {
-        const unsigned w = sw[i];
-        if (w) {
-          const unsigned long long key = skey[i];
-          if (shift == 56 || (key >> (shift + 8)) == (prefix >> (shift + 8)))
-            atomicAdd(&hist[(key >> shift) & 255ull], (unsigned long long)w);
-        }
-      }
-      __syncthreads();
-      if (wave == 0) {
-        // lane l owns the descending bins 4l .. 4l+3 (bin index 255-4l-k)
-        long long v[4], s4 = 0;
 #pragma unroll
-        for (int k = 0; k < 4; ++k) { v[k] = (long long)hist[255 - 4 * lane - k]; s4 += v[k]; }
-        long long incl = s4;
+      for (int k = 0; k < 4; ++k) { hist[4 * lane + k] = 0ull; hcnt[4 * lane + k] = 0u; }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      if (in_regs) {
 #pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-          const long long up = shfl_up_i64(incl, o);
-          if (lane >= o) incl += up;
-        }
-        long long before = incl - s4;
-        const long long want = (long long)sel[1];
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-          if (before < want && want <= before + v[k]) {
-            sel[0] = prefix | ((unsigned long long)(255 - 4 * lane - k) << shift);
-            sel[1] = (unsigned long long)(want - before);
+        for (int u = 0; u < kRegSegs; ++u)
+          if (rw[u] && (shift == 56 || (rkey[u] >> (shift + 8)) == (prefix >> (shift + 8)))) {
+            atomicAdd(&hist[(rkey[u] >> shift) & 255ull], (unsigned long long)rw[u]);
+            atomicAdd(&hcnt[(rkey[u] >> shift) & 255ull], 1u);
           }
-          before += v[k];
+      } else {
+        for (int64_t i = lane; i < nseg; i += 64) {
+          const unsigned w = sw[i];
+          if (w) {
+            const unsigned long long key = skey[i];
+            if (shift == 56 || (key >> (shift + 8)) == (prefix >> (shift + 8)))
+              atomicAdd(&hist[(key >> shift) & 255ull], (unsigned long long)w);
+          }
         }
       }
-      __syncthreads();
+      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      // lane l owns the descending bins 4l .. 4l+3 (bin index 255-4l-k)
+      long long v[4], s4 = 0;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) { v[k] = (long long)hist[255 - 4 * lane - k]; s4 += v[k]; }
+      long long incl = s4;
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) {
+        const long long up = shfl_up_i64(incl, o);
+        if (lane >= o) incl += up;
+      }
+      long long before = incl - s4;
+      int found_bin = -1;
+      long long found_rem = 0;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        if (before < want && want <= before + v[k]) { found_bin = 255 - 4 * lane - k; found_rem = want - before; }
+        before += v[k];
+      }
+      const unsigned long long who = __ballot(found_bin >= 0);   // exactly one lane
+      const int src = __ffsll((long long)who) - 1;
+      const int bin = __shfl(found_bin, src);
+      want = shfl_i64(found_rem, src);
+      prefix |= (unsigned long long)bin << shift;
+      if (in_regs && hcnt[bin] == 1u) {
+        // a single segment is left in the chosen bin: its key is g*, no further digits needed
+        unsigned long long mine = 0ull;
+#pragma unroll
+        for (int u = 0; u < kRegSegs; ++u)
+          if (rw[u] && (rkey[u] >> shift) == (prefix >> shift)) mine = rkey[u];
+        const unsigned long long owner = __ballot(mine != 0ull);
+        prefix = (unsigned long long)shfl_i64((long long)mine, __ffsll((long long)owner) - 1);
+        break;
+      }
+      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+      __builtin_amdgcn_wave_barrier();
     }
+    if (lane == 0) { sel[0] = prefix; sel[1] = (unsigned long long)want; }
   }
+  __syncthreads();
   const unsigned long long kstar = sel[0];
   const long long rem = active ? (long long)sel[1] : 0;
 
   // budgets: everything above g*, ties at g* in head order
+  long long* h_gt = reinterpret_cast<long long*>(l_vtx);   // flags are dead by now: reuse for per-head sums
+  long long* h_eq = h_gt + NH;
+  const bool head_lds = small && (int64_t)NH * 16 <= nseg * 4;
+  if (head_lds) {
+    for (int h = t; h < NH; h += nt) { h_gt[h] = 0; h_eq[h] = 0; }
+    __syncthreads();
+    if (active) {
+      for (int i = t; i < (int)nseg; i += nt) {
+        const unsigned w = sw[i];
+        if (w) {
+          const unsigned long long key = skey[i];
+          if (key > kstar) atomicAdd(reinterpret_cast<unsigned long long*>(&h_gt[i / Gp]), (unsigned long long)w);
+          else if (key == kstar) atomicAdd(reinterpret_cast<unsigned long long*>(&h_eq[i / Gp]), (unsigned long long)w);
+        }
+      }
+    }
+    __syncthreads();
+  }
   long long carry = 0;
-  for (int h0 = 0; h0 < NH; h0 += 256) {
+  for (int h0 = 0; h0 < NH; h0 += nt) {
     const int h = h0 + t;
     long long gt = 0, eq = 0;
     if (h < NH && active) {
-      for (int e = 0; e < Gp; ++e) {
-        const unsigned w = sw[(int64_t)h * Gp + e];
-        const unsigned long long key = skey[(int64_t)h * Gp + e];
-        if (key > kstar) gt += w;
-        else if (key == kstar) eq += w;
+      if (head_lds) {
+        gt = h_gt[h];
+        eq = h_eq[h];
+      } else {
+        for (int e = 0; e < Gp; ++e) {
+          const unsigned w = sw[(int64_t)h * Gp + e];
+          const unsigned long long key = skey[(int64_t)h * Gp + e];
+          if (key > kstar) gt += w;
+          else if (key == kstar) eq += w;
+        }
       }
     }
     long long tot;

@@ -4,10 +4,12 @@
 
 namespace lukv {
 
-__global__ __launch_bounds__(256) void allocate_kernel(AllocIO io) {
+__global__ __launch_bounds__(256) void allocate_vertices_kernel(AllocIO io, int blocks_per_problem) {
+  alloc_phase_a(io, blockIdx.x / blocks_per_problem, blockIdx.x % blocks_per_problem);
+}
+
+__global__ __launch_bounds__(256) void allocate_budgets_kernel(AllocIO io) {
   __shared__ __align__(16) char lds[32768];
-  alloc_phase_a(io, blockIdx.x, lds, (int)sizeof(lds));
-  __syncthreads();
   alloc_phase_b(io, blockIdx.x, lds, (int)sizeof(lds));
 }
 
@@ -43,14 +45,16 @@ AllocIO make_alloc_io(int32_t n_problems, int32_t n_heads, int32_t n_grid, const
   io.status = status;
   io.seg_key = reinterpret_cast<unsigned long long*>(ws + lay.seg_key);
   io.seg_w = reinterpret_cast<unsigned*>(ws + lay.seg_w);
-  io.meta = reinterpret_cast<long long*>(ws + lay.alloc_meta);
+  io.vertex = reinterpret_cast<int32_t*>(ws + lay.alloc_vertex);
   for (int i = 0; i < LUKV_MAX_SEQS; ++i) io.B[i] = (B_total && i < n_problems) ? B_total[i] : 0;
   return io;
 }
 
 int launch_allocate(const AllocIO& io, hipStream_t st) {
   stage_mark(kStAllocate, st);
-  hipLaunchKernelGGL(allocate_kernel, dim3(io.n_problems), dim3(256), 0, st, io);
+  const int bpp = alloc_blocks_a(io.n_heads, io.n_grid);
+  hipLaunchKernelGGL(allocate_vertices_kernel, dim3(io.n_problems * bpp), dim3(256), 0, st, io, bpp);
+  hipLaunchKernelGGL(allocate_budgets_kernel, dim3(io.n_problems), dim3(256), 0, st, io);
   hipLaunchKernelGGL(offsets_kernel, dim3(1), dim3(256), 0, st, (const int32_t*)io.budgets, io.offsets,
                      (int64_t)io.n_problems * io.n_heads);
   return check_launch();

@@ -97,7 +97,6 @@ WsLayout make_layout(const HostCfg& hc, int32_t n_grid, bool alloc_only) {
   int64_t off = 0;
   auto take = [&](int64_t bytes) { const int64_t o = off; off = align_up(off + bytes, 256); return o; };
   const int64_t n_sel = alloc_only ? 0 : w.n_hi;
-  w.alloc_meta = take(LUKV_MAX_SEQS * 4 * 8);
   w.hist = take(n_sel * w.max_slices * (kHistBins / 2) * 4);
   w.partial = take((int64_t)w.n_hi * w.max_chunks * w.rows_padded * 8);
   const int64_t score_bytes = (int64_t)g.n_layers * g.n_kv_heads * g.total_tokens * 4;
@@ -106,7 +105,7 @@ WsLayout make_layout(const HostCfg& hc, int32_t n_grid, bool alloc_only) {
   w.sel_state = take(n_sel * 16);
   w.slice_cnt = take(n_sel * w.max_blocks * 8);
   const int64_t nseg = (int64_t)hc.n_hi * (n_grid > 0 ? n_grid : 0);
-  w.hull = take(nseg * 4);
+  w.alloc_vertex = take(nseg * 4);
   w.seg_key = take(nseg * 8);
   w.seg_w = take(nseg * 4);
   w.total = off;
@@ -209,7 +208,7 @@ int lukv_select_compact(const lukv_config* cfg, const float* pooled, const int32
   const WsLayout lay = make_layout(hc, 0, false);
   if ((rc = check_ws(lay, ws, ws_bytes))) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  return launch_select_compact(hc, lay, pooled, false, nullptr, budgets, const_cast<int64_t*>(offsets),
+  return launch_select_compact(hc, lay, nullptr, pooled, false, nullptr, budgets, const_cast<int64_t*>(offsets),
                                false, k, v, kept_idx, k_out, v_out, out_rows, status, (char*)ws, st);
 }
 
@@ -238,13 +237,14 @@ int lukv_evict(const lukv_config* cfg, const void* q_win, const void* k, const v
   char* w = (char*)ws;
   float* scores = pooled ? pooled : reinterpret_cast<float*>(w + lay.pooled);
   int32_t* sel_status = status + cfg->n_seqs;
-  // the allocation never looks at scores: its two phases ride along as extra workgroups of
-  // the two score kernels; selection pools the raw metric on the fly
+  // the allocation never looks at scores: its two phases ride along as a few extra workgroups
+  // of the second score kernel and of the first selection kernel (where they do not displace
+  // resident scoring workgroups); selection pools the raw metric on the fly
   const int n_heads = hc.g.n_layers * hc.g.n_kv_heads;
   const AllocIO aio = make_alloc_io(cfg->n_seqs, n_heads, n_grid, curves, knots, b_min, b_max, B_total,
                                     budgets, offsets, status, lay, w);
   if ((rc = launch_score_raw(hc, lay, q_win, k, &aio, w, st))) return rc;
-  rc = launch_select_compact(hc, lay, reinterpret_cast<const float*>(w + lay.raw), true, scores, budgets,
+  rc = launch_select_compact(hc, lay, &aio, reinterpret_cast<const float*>(w + lay.raw), true, scores, budgets,
                              offsets, true, k, v, kept_idx, k_out, v_out, out_rows, sel_status, w, st);
   stage_mark(kStEnd, st);
   return rc;

@@ -45,14 +45,13 @@ struct Geom {
 
 // Byte offsets into the caller's workspace.
 struct WsLayout {
-  int64_t alloc_meta;            // i64 [LUKV_MAX_SEQS * 4]
+  int64_t alloc_vertex;          // i32 [n_problems * n_heads * n_grid]
   int64_t hist;                  // u32 [n_hi * max_slices * kHistBins / 2] packed 16-bit counts
   int64_t partial;               // float2 [n_hi * max_chunks * rows_padded]
   int64_t raw;                   // float [n_layers * n_kv_heads * total_tokens]
   int64_t pooled;                // float, same shape
   int64_t sel_state;             // uint4 [n_hi]
   int64_t slice_cnt;             // uint2 [n_hi * max_blocks]
-  int64_t hull;                  // i32 [n_problems * n_heads * n_grid]
   int64_t seg_key;               // u64 [n_problems * n_heads * n_grid]
   int64_t seg_w;                 // u32 [n_problems * n_heads * n_grid]
   int64_t total;
@@ -72,11 +71,14 @@ SeqTab tiles_for(const SeqTab& seq, int tile, int shrink);  // tiles over (L_s -
 
 // Launchers (enqueue only; return a LUKV_* code).
 struct AllocIO;
-// raw (unpooled) metric into the workspace; aio != NULL also runs the allocation alongside
+// raw (unpooled) metric into the workspace; aio != NULL: the allocation's first phase rides
+// along in the second score kernel
 int launch_score_raw(const HostCfg& hc, const WsLayout& lay, const void* q, const void* k,
                      const AllocIO* aio, char* ws, hipStream_t st);
 int launch_pool(const HostCfg& hc, const WsLayout& lay, float* pooled_out, char* ws, hipStream_t st);
-int launch_select_compact(const HostCfg& hc, const WsLayout& lay, const float* scores_in, bool pool,
+// aio != NULL: the allocation's second phase rides along in the first selection kernel
+int launch_select_compact(const HostCfg& hc, const WsLayout& lay, const AllocIO* aio,
+                          const float* scores_in, bool pool,
                           float* pooled_out, const int32_t* budgets, int64_t* offsets,
                           bool make_offsets, const void* k, const void* v, int32_t* kept_idx, void* k_out, void* v_out,
                           int64_t out_rows, int32_t* status, char* ws, hipStream_t st);

@@ -22,8 +22,8 @@
 // "half hf = l/32 owns elements [hf*D/2, (hf+1)*D/2) of the row", so any internal ordering
 // of k is the same on both sides.  Output: acc[v] is row 8*(v/4) + 4*(l/32) + v%4, column l%32.
 //
-// When the fused path asks for it, the first blockIdx.x values of the two kernels run the
-// two phases of the budget allocation instead of scoring (they do not depend on scores).
+// When the fused path asks for it, the first blockIdx.x values of the second kernel run the
+// first phase of the budget allocation instead of scoring (it does not depend on scores).
 #include <string.h>
 
 #include "alloc_device.hpp"
@@ -116,27 +116,15 @@ __device__ __forceinline__ void merge_stats(float& m, float& z, float m2, float 
 
 // ---- pass A: softmax statistics ----------------------------------------------------------
 template <bool F32, int D, int NBM, int RG>
-__global__ __launch_bounds__(256) void score_stats_kernel(Geom g, SeqTab tab, AllocIO aio,
-                                                          int n_alloc_blocks, const char* q,
+__global__ __launch_bounds__(256) void score_stats_kernel(Geom g, SeqTab tab, const char* q,
                                                           const char* k, float2* partial,
                                                           int max_chunks, int rows_padded) {
   using T = Tile<F32, D, RG>;
-  // at least 32 KiB: the allocation phase borrows the tile as scratch (hull stacks)
-  constexpr int kTileU4 = T::kKeys * T::kLdsRowU4 > 2048 ? T::kKeys * T::kLdsRowU4 : 2048;
-  __shared__ u32x4 ktile[kTileU4];
+  __shared__ u32x4 ktile[T::kKeys * T::kLdsRowU4];
   __shared__ float2 wstat[4][NBM][32];
 
-  if ((int)blockIdx.x < n_alloc_blocks) {
-    if (blockIdx.y == 0 && blockIdx.z == 0) {
-      // a short latency-bound job sharing its CU with throughput-bound scoring waves:
-      // let it issue whenever it is ready so that it finishes well inside this launch
-      __builtin_amdgcn_s_setprio(3);
-      alloc_phase_a(aio, blockIdx.x, reinterpret_cast<char*>(ktile), (int)sizeof(ktile));
-    }
-    return;
-  }
   int seq, ch;
-  find_tile(tab, blockIdx.x - n_alloc_blocks, seq, ch);
+  find_tile(tab, blockIdx.x, seq, ch);
   const int kvh = blockIdx.y, layer = blockIdx.z;
   const int tok0 = tab.cu[seq], L = tab.cu[seq + 1] - tok0, P = L - g.window;
   const int hi = (seq * g.n_layers + layer) * g.n_kv_heads + kvh;
@@ -234,22 +222,21 @@ __global__ __launch_bounds__(256) void score_stats_kernel(Geom g, SeqTab tab, Al
 // ---- pass B: normalised window sums ------------------------------------------------------
 template <bool F32, int D, int NBM, int RG>
 __global__ __launch_bounds__(256) void score_accum_kernel(Geom g, SeqTab tab, AllocIO aio,
-                                                          int n_alloc_blocks, const char* q,
+                                                          int n_alloc_blocks, int alloc_bpp,
+                                                          const char* q,
                                                           const char* k, const float2* partial,
                                                           float* raw, int max_chunks,
                                                           int rows_padded) {
   using T = Tile<F32, D, RG>;
-  constexpr int kTileU4 = T::kKeys * T::kLdsRowU4 > 2048 ? T::kKeys * T::kLdsRowU4 : 2048;
-  __shared__ u32x4 ktile[kTileU4];
+  __shared__ u32x4 ktile[T::kKeys * T::kLdsRowU4];
   __shared__ __align__(16) float rowc_s[kMaxRows];
   __shared__ float2 pm[kMaxRows];
   __shared__ float colred[4][32];
 
   if ((int)blockIdx.x < n_alloc_blocks) {
-    if (blockIdx.y == 0 && blockIdx.z == 0) {
-      __builtin_amdgcn_s_setprio(3);
-      alloc_phase_b(aio, blockIdx.x, reinterpret_cast<char*>(ktile), (int)sizeof(ktile));
-    }
+    // a few short extra workgroups: hull vertices of the budget allocation (no use of scores)
+    if (blockIdx.y == 0 && blockIdx.z == 0)
+      alloc_phase_a(aio, blockIdx.x / alloc_bpp, blockIdx.x % alloc_bpp);
     return;
   }
   int seq, ch;
@@ -390,17 +377,17 @@ static int launch_raw_t(const HostCfg& hc, const WsLayout& lay, const void* q, c
   const SeqTab tabB = tiles_for(hc.seq, g.chunk_keys, g.window);
   AllocIO io;
   memset(&io, 0, sizeof(io));
-  int n_alloc = 0;
-  if (aio) { io = *aio; n_alloc = aio->n_problems; }
-  dim3 gridA(tabA.tile0[tabA.n_seqs] + n_alloc, g.n_kv_heads, g.n_layers);
+  int n_alloc = 0, bpp = 1;
+  if (aio) { io = *aio; bpp = alloc_blocks_a(aio->n_heads, aio->n_grid); n_alloc = aio->n_problems * bpp; }
+  dim3 gridA(tabA.tile0[tabA.n_seqs], g.n_kv_heads, g.n_layers);
   dim3 gridB(tabB.tile0[tabB.n_seqs] + n_alloc, g.n_kv_heads, g.n_layers);
   stage_mark(kStStats, st);
-  hipLaunchKernelGGL((score_stats_kernel<F32, D, NBM, RG>), gridA, dim3(256), 0, st, g, tabA, io,
-                     n_alloc, (const char*)q, (const char*)k, partial, lay.max_chunks,
+  hipLaunchKernelGGL((score_stats_kernel<F32, D, NBM, RG>), gridA, dim3(256), 0, st, g, tabA,
+                     (const char*)q, (const char*)k, partial, lay.max_chunks,
                      lay.rows_padded);
   stage_mark(kStAccum, st);
   hipLaunchKernelGGL((score_accum_kernel<F32, D, NBM, RG>), gridB, dim3(256), 0, st, g, tabB, io,
-                     n_alloc, (const char*)q, (const char*)k, (const float2*)partial, raw,
+                     n_alloc, bpp, (const char*)q, (const char*)k, (const float2*)partial, raw,
                      lay.max_chunks, lay.rows_padded);
   return check_launch();
 }

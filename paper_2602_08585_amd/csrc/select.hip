@@ -2,7 +2,8 @@
 // with the fixed tie rule App. A.1 assumes (lowest position first), and the gather of the
 // retained rows into a dense per-head cache (Sec. 3.2, Eq. 3).
 //
-// Exact radix select on order-preserving 32-bit keys, digits of 11, 11 and 10 bits.
+// Exact radix select on order-preserving 32-bit keys: an 11-bit top digit, then up to two
+// digits over the bits in which the surviving keys still differ.
 //   sel_hist - one workgroup (1024 threads) per slice of 1024 scores: [optionally the clipped
 //              max-pool + forced +inf of step 1,] an LDS histogram of the top digit, stored
 //              as the slice's own 16-bit counts (no shared hot counters).
@@ -13,6 +14,9 @@
 //   sel_emit - one workgroup per block of 256 scores: prefix over earlier blocks, keep
 //              (key > T) plus the first r ties by position, write ascending positions and
 //              copy the K and V rows (16 bytes per lane, eight rows in flight per thread).
+#include <string.h>
+
+#include "alloc_device.hpp"
 #include "lukv_internal.hpp"
 
 namespace lukv {
@@ -21,6 +25,20 @@ __device__ __forceinline__ unsigned key_of(float f) {
   unsigned u = __float_as_uint(f);
   if (u == 0x80000000u) u = 0u;  // -0 and +0 tie
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+// Histogram increment that does not serialise when a whole wave hits one bin (pooled scores
+// come in runs of equal values, and a narrow score range puts every key in the same digit).
+__device__ __forceinline__ void hist_add(unsigned* lh, unsigned bin, bool act) {
+  const unsigned long long m = __ballot(act);
+  if (m == 0ull) return;
+  const int leader = __ffsll((long long)m) - 1;
+  const unsigned first = (unsigned)__shfl((int)bin, leader);
+  if (__ballot(act && bin != first) == 0ull) {
+    if ((int)(threadIdx.x & 63) == leader) atomicAdd(&lh[first], (unsigned)__popcll(m));
+  } else if (act) {
+    atomicAdd(&lh[bin], 1u);
+  }
 }
 
 struct SelGeom {
@@ -47,13 +65,20 @@ __device__ __forceinline__ unsigned scan1024(unsigned v, unsigned* part) {
 
 // Slice histogram of the top digit (and, with POOL, the pooled scores themselves).
 template <bool POOL>
-__global__ __launch_bounds__(1024) void sel_hist_kernel(SelGeom sg, SeqTab tab, const float* src_scores,
+__global__ __launch_bounds__(1024) void sel_hist_kernel(SelGeom sg, SeqTab tab, AllocIO aio,
+                                                        int n_alloc_blocks, const float* src_scores,
                                                         float* pooled_out, unsigned* hist_parts,
                                                         int32_t* status) {
-  __shared__ unsigned lh[kHistBins];
-  __shared__ float rawt[kSliceElems + 32];
+  __shared__ __align__(16) char scratch[32768];
+  unsigned* lh = reinterpret_cast<unsigned*>(scratch);                      // kHistBins counters
+  float* rawt = reinterpret_cast<float*>(scratch + kHistBins * 4);           // slice + pool halo
+  if ((int)blockIdx.x < n_alloc_blocks) {
+    // extra workgroups of the fused path: budgets of one allocation problem each
+    if (blockIdx.y == 0 && blockIdx.z == 0) alloc_phase_b(aio, blockIdx.x, scratch, (int)sizeof(scratch));
+    return;
+  }
   int seq, sl;
-  find_tile(tab, blockIdx.x, seq, sl);
+  find_tile(tab, blockIdx.x - n_alloc_blocks, seq, sl);
   const int kvh = blockIdx.y, layer = blockIdx.z, t = threadIdx.x;
   const int tok0 = tab.cu[seq], L = tab.cu[seq + 1] - tok0;
   const int hi = (seq * sg.n_layers + layer) * sg.n_kv_heads + kvh;
@@ -62,7 +87,7 @@ __global__ __launch_bounds__(1024) void sel_hist_kernel(SelGeom sg, SeqTab tab, 
   float* pooled = POOL ? pooled_out + base : nullptr;
   unsigned* my_part = hist_parts + ((int64_t)hi * sg.max_slices + sl) * (kHistBins / 2);
   // the selection status word starts at zero; later kernels of the call only OR into it
-  if (t == 0 && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0) *status = 0;
+  if (t == 0 && (int)blockIdx.x == n_alloc_blocks && blockIdx.y == 0 && blockIdx.z == 0) *status = 0;
 
   lh[t] = 0;
   lh[t + 1024] = 0;
@@ -88,7 +113,7 @@ __global__ __launch_bounds__(1024) void sel_hist_kernel(SelGeom sg, SeqTab tab, 
     __syncthreads();
     if (j < L) s = src[j];
   }
-  if (j < L) atomicAdd(&lh[key_of(s) >> 21], 1u);
+  hist_add(lh, key_of(s) >> 21, j < L);
   __syncthreads();
   my_part[t] = (lh[2 * t] & 0xFFFFu) | (lh[2 * t + 1] << 16);   // counts <= 1024 fit 16 bits
 }
@@ -96,22 +121,42 @@ __global__ __launch_bounds__(1024) void sel_hist_kernel(SelGeom sg, SeqTab tab, 
 // One workgroup per head: fixes the threshold key T and the number of ties to keep,
 // state[hi] = {T, ties at T to keep, budget after clamping, 0}, counts per block of 256
 // scores, and (if offsets_out is given) this head's row offset = sum of the budgets before it.
+// A thread owns the keys j = r*32768 + u*1024 + t (u < 32) of round r; with ONE (L <= 32768)
+// they are loaded once, all 32 loads in flight together, and stay in registers for every
+// phase; longer heads re-read them round by round.
+template <bool ONE>
 __global__ __launch_bounds__(1024) void sel_tail_kernel(SelGeom sg, SeqTab tab, const float* scores,
                                                         const int32_t* budgets, const unsigned* hist_parts,
                                                         uint4* state, uint2* block_cnt,
                                                         int64_t* offsets_out, int n_heads_total,
                                                         int32_t* status) {
+  constexpr int KPT = 32;
   __shared__ unsigned lh[kHistBins];
   __shared__ unsigned part[16];
   __shared__ unsigned sel[2];
   __shared__ long long osum[16];
+  __shared__ unsigned short cg[16][KPT], ce[16][KPT];
   const int hi = blockIdx.x, t = threadIdx.x;
   const int kvh = hi % sg.n_kv_heads, layer = (hi / sg.n_kv_heads) % sg.n_layers;
   const int seq = hi / (sg.n_kv_heads * sg.n_layers);
   const int tok0 = tab.cu[seq], L = tab.cu[seq + 1] - tok0;
   const int n_slices = (L + kSliceElems - 1) / kSliceElems;
+  const int n_rounds = (L + 1024 * KPT - 1) / (1024 * KPT);
   const float* keys_src = scores + ((int64_t)layer * sg.n_kv_heads + kvh) * sg.total_tokens + tok0;
   const int lane = t & 63, wave = t >> 6;
+
+  unsigned key[KPT];   // order-preserving keys of this thread's scores (0 beyond L: below every real key's use)
+  auto load_round = [&](int r) {
+    float f[KPT];
+#pragma unroll
+    for (int u = 0; u < KPT; ++u) {
+      const int jj = (r * KPT + u) * 1024 + t;
+      f[u] = jj < L ? keys_src[jj] : 0.f;
+    }
+#pragma unroll
+    for (int u = 0; u < KPT; ++u) key[u] = key_of(f[u]);
+  };
+  if (ONE) load_round(0);
 
   if (offsets_out) {
     long long acc = 0;
@@ -147,12 +192,12 @@ __global__ __launch_bounds__(1024) void sel_tail_kernel(SelGeom sg, SeqTab tab, 
   unsigned c_hi = 0, c_lo = 0;
   {
     const unsigned* hp = hist_parts + (int64_t)hi * sg.max_slices * (kHistBins / 2) + (1023 - t);
-    for (int s0 = 0; s0 < n_slices; s0 += 8) {
-      unsigned w[8];   // independent loads first: one memory latency per eight slices
+    for (int s0 = 0; s0 < n_slices; s0 += 32) {
+      unsigned w[32];   // independent loads first: one memory latency per 32 slices
 #pragma unroll
-      for (int u = 0; u < 8; ++u) w[u] = s0 + u < n_slices ? hp[(int64_t)(s0 + u) * (kHistBins / 2)] : 0u;
+      for (int u = 0; u < 32; ++u) w[u] = s0 + u < n_slices ? hp[(int64_t)(s0 + u) * (kHistBins / 2)] : 0u;
 #pragma unroll
-      for (int u = 0; u < 8; ++u) { c_lo += w[u] & 0xFFFFu; c_hi += w[u] >> 16; }
+      for (int u = 0; u < 32; ++u) { c_lo += w[u] & 0xFFFFu; c_hi += w[u] >> 16; }
     }
   }
   unsigned want = (unsigned)kb, prefix = 0;
@@ -164,78 +209,108 @@ __global__ __launch_bounds__(1024) void sel_tail_kernel(SelGeom sg, SeqTab tab, 
     prefix = sel[0] << 21;
     want = sel[1];
   }
-  // digit 1 (bits 20..10) among keys with the same digit 0
-  lh[t] = 0;
-  lh[t + 1024] = 0;
-  __syncthreads();
-  for (int jj0 = t; jj0 < L; jj0 += 8 * 1024) {
-    float f[8];
-#pragma unroll
-    for (int u = 0; u < 8; ++u) f[u] = jj0 + u * 1024 < L ? keys_src[jj0 + u * 1024] : 0.f;
-#pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      const unsigned key = key_of(f[u]);
-      if (jj0 + u * 1024 < L && (key >> 21) == (prefix >> 21)) atomicAdd(&lh[(key >> 10) & 2047u], 1u);
-    }
-  }
+  // The keys that share digit 0 usually differ only in some low bits: find the bits in which
+  // they vary at all and spread those over the remaining digits (at most 11 + 10 bits), so
+  // that a narrow range of scores still fills the histogram evenly.
+  if (t < 2) sel[t] = t == 0 ? 0xFFFFFFFFu : 0u;   // min, max of the candidate keys
   __syncthreads();
   {
-    const unsigned a1 = lh[2047 - 2 * t], a0 = lh[2046 - 2 * t];
-    const unsigned before = scan1024(a1 + a0, part);
-    if (before < want && want <= before + a1) { sel[0] = 2047 - 2 * t; sel[1] = want - before; }
-    else if (before + a1 < want && want <= before + a1 + a0) { sel[0] = 2046 - 2 * t; sel[1] = want - before - a1; }
-    __syncthreads();
-    prefix |= sel[0] << 10;
-    want = sel[1];
-  }
-  // digit 2 (bits 9..0)
-  __syncthreads();
-  lh[t] = 0;
-  __syncthreads();
-  for (int jj0 = t; jj0 < L; jj0 += 8 * 1024) {
-    float f[8];
+    unsigned cmin = 0xFFFFFFFFu, cmax = 0u;
+    for (int r = 0; r < n_rounds; ++r) {
+      if (!ONE) load_round(r);
 #pragma unroll
-    for (int u = 0; u < 8; ++u) f[u] = jj0 + u * 1024 < L ? keys_src[jj0 + u * 1024] : 0.f;
-#pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      const unsigned key = key_of(f[u]);
-      if (jj0 + u * 1024 < L && (key >> 10) == (prefix >> 10)) atomicAdd(&lh[key & 1023u], 1u);
-    }
-  }
-  __syncthreads();
-  {
-    const unsigned a = lh[1023 - t];
-    const unsigned before = scan1024(a, part);
-    if (before < want && want <= before + a) { sel[0] = 1023 - t; sel[1] = want - before; }
-    __syncthreads();
-    prefix |= sel[0];
-    want = sel[1];
-  }
-  const unsigned T = prefix;
-  if (t == 0) state[hi] = make_uint4(T, want, (unsigned)kb, 0u);
-  // per block of 256 scores: keys above T and keys equal to T (one wave per block)
-  const int n_blocks = (L + kEmitElems - 1) / kEmitElems;
-  for (int b = wave; b < n_blocks; b += 16) {
-    unsigned gt = 0, eq = 0;
-    float f[kEmitElems / 64];
-#pragma unroll
-    for (int i = 0; i < kEmitElems / 64; ++i) {
-      const int jj = b * kEmitElems + i * 64 + lane;
-      f[i] = jj < L ? keys_src[jj] : 0.f;
-    }
-#pragma unroll
-    for (int i = 0; i < kEmitElems / 64; ++i) {
-      const int jj = b * kEmitElems + i * 64 + lane;
-      const unsigned key = key_of(f[i]);
-      gt += jj < L && key > T;
-      eq += jj < L && key == T;
+      for (int u = 0; u < KPT; ++u)
+        if ((r * KPT + u) * 1024 + t < L && (key[u] >> 21) == (prefix >> 21)) {
+          cmin = key[u] < cmin ? key[u] : cmin;
+          cmax = key[u] > cmax ? key[u] : cmax;
+        }
     }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) {
-      gt += __shfl_xor(gt, o);
-      eq += __shfl_xor(eq, o);
+      const unsigned a2 = (unsigned)__shfl_xor((int)cmin, o), b2 = (unsigned)__shfl_xor((int)cmax, o);
+      cmin = a2 < cmin ? a2 : cmin;
+      cmax = b2 > cmax ? b2 : cmax;
     }
-    if (lane == 0) block_cnt[(int64_t)hi * sg.max_blocks + b] = make_uint2(gt, eq);
+    if (lane == 0) { atomicMin(&sel[0], cmin); atomicMax(&sel[1], cmax); }
+  }
+  __syncthreads();
+  const unsigned cand_min = sel[0], vary = sel[0] ^ sel[1];
+  __syncthreads();
+  if (vary == 0u) {
+    prefix = cand_min;             // every candidate is the same key: T is that key, `want` ties
+  } else {
+    const int vb = 31 - __clz(vary);                    // top varying bit (<= 20)
+    const int shift1 = vb > 10 ? vb - 10 : 0;           // digit 1: bits vb .. shift1
+    const unsigned mask1 = (2u << (vb - shift1)) - 1u;
+    prefix = cand_min & ~((2u << vb) - 1u);             // bits above vb are common
+    lh[t] = 0;
+    lh[t + 1024] = 0;
+    __syncthreads();
+    for (int r = 0; r < n_rounds; ++r) {
+      if (!ONE) load_round(r);
+#pragma unroll
+      for (int u = 0; u < KPT; ++u)
+        if ((r * KPT + u) * 1024 + t < L && (key[u] >> (vb + 1)) == (prefix >> (vb + 1)))
+          atomicAdd(&lh[(key[u] >> shift1) & mask1], 1u);
+    }
+    __syncthreads();
+    {
+      const unsigned a1 = lh[2047 - 2 * t], a0 = lh[2046 - 2 * t];
+      const unsigned before = scan1024(a1 + a0, part);
+      if (before < want && want <= before + a1) { sel[0] = 2047 - 2 * t; sel[1] = want - before; }
+      else if (before + a1 < want && want <= before + a1 + a0) { sel[0] = 2046 - 2 * t; sel[1] = want - before - a1; }
+      __syncthreads();
+      prefix |= sel[0] << shift1;
+      want = sel[1];
+    }
+    if (shift1 > 0) {
+      // digit 2: the remaining low bits (at most 10)
+      __syncthreads();
+      lh[t] = 0;
+      __syncthreads();
+      const unsigned mask2 = (1u << shift1) - 1u;
+      for (int r = 0; r < n_rounds; ++r) {
+        if (!ONE) load_round(r);
+#pragma unroll
+        for (int u = 0; u < KPT; ++u)
+          if ((r * KPT + u) * 1024 + t < L && (key[u] >> shift1) == (prefix >> shift1))
+            atomicAdd(&lh[key[u] & mask2], 1u);
+      }
+      __syncthreads();
+      {
+        const unsigned a = lh[1023 - t];
+        const unsigned before = scan1024(a, part);
+        if (before < want && want <= before + a) { sel[0] = 1023 - t; sel[1] = want - before; }
+        __syncthreads();
+        prefix |= sel[0];
+        want = sel[1];
+      }
+    }
+  }
+  const unsigned T = prefix;
+  if (t == 0) state[hi] = make_uint4(T, want, (unsigned)kb, 0u);
+  // per block of 256 scores: keys above T and keys equal to T.  Key (r, u, t) sits in block
+  // (r*KPT + u)*4 + t/256: four waves share a block, ballots count, LDS joins the four.
+  for (int r = 0; r < n_rounds; ++r) {
+    if (!ONE) load_round(r);
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < KPT; ++u) {
+      const bool in = (r * KPT + u) * 1024 + t < L;
+      const unsigned long long mg = __ballot(in && key[u] > T), me = __ballot(in && key[u] == T);
+      if (lane == 0) { cg[wave][u] = (unsigned short)__popcll(mg); ce[wave][u] = (unsigned short)__popcll(me); }
+    }
+    __syncthreads();
+    if (t < 4 * KPT) {
+      const int u = t >> 2, q = t & 3;
+      const int b = (r * KPT + u) * 4 + q;
+      if (b * kEmitElems < L) {
+        unsigned gt = 0, eq = 0;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) { gt += cg[4 * q + w][u]; eq += ce[4 * q + w][u]; }
+        block_cnt[(int64_t)hi * sg.max_blocks + b] = make_uint2(gt, eq);
+      }
+    }
   }
 }
 
@@ -347,7 +422,8 @@ static void launch_emit(dim3 grid, hipStream_t st, SelGeom sg, const SeqTab& tab
 
 // scores_in: pooled scores (pool = false) or the unpooled metric (pool = true; the pooled
 // scores are then written to pooled_out and used for the selection).
-int launch_select_compact(const HostCfg& hc, const WsLayout& lay, const float* scores_in, bool pool,
+int launch_select_compact(const HostCfg& hc, const WsLayout& lay, const AllocIO* aio,
+                          const float* scores_in, bool pool,
                           float* pooled_out, const int32_t* budgets, int64_t* offsets, bool make_offsets,
                           const void* k, const void* v, int32_t* kept_idx, void* k_out, void* v_out,
                           int64_t out_rows, int32_t* status, char* ws, hipStream_t st) {
@@ -359,20 +435,29 @@ int launch_select_compact(const HostCfg& hc, const WsLayout& lay, const float* s
   unsigned* hist = reinterpret_cast<unsigned*>(ws + lay.hist);
   uint4* state = reinterpret_cast<uint4*>(ws + lay.sel_state);
   uint2* block_cnt = reinterpret_cast<uint2*>(ws + lay.slice_cnt);
-  dim3 gridH(tabH.tile0[tabH.n_seqs], g.n_kv_heads, g.n_layers);
+  AllocIO io;
+  memset(&io, 0, sizeof(io));
+  int n_alloc = 0;
+  if (aio) { io = *aio; n_alloc = aio->n_problems; }
+  dim3 gridH(tabH.tile0[tabH.n_seqs] + n_alloc, g.n_kv_heads, g.n_layers);
   dim3 gridE(tabE.tile0[tabE.n_seqs], g.n_kv_heads, g.n_layers);
   stage_mark(kStHist, st);
   if (pool)
-    hipLaunchKernelGGL(sel_hist_kernel<true>, gridH, dim3(1024), 0, st, sg, tabH, scores_in, pooled_out,
-                       hist, status);
+    hipLaunchKernelGGL(sel_hist_kernel<true>, gridH, dim3(1024), 0, st, sg, tabH, io, n_alloc, scores_in,
+                       pooled_out, hist, status);
   else
-    hipLaunchKernelGGL(sel_hist_kernel<false>, gridH, dim3(1024), 0, st, sg, tabH, scores_in,
+    hipLaunchKernelGGL(sel_hist_kernel<false>, gridH, dim3(1024), 0, st, sg, tabH, io, n_alloc, scores_in,
                        (float*)nullptr, hist, status);
   const float* sel_scores = pool ? pooled_out : scores_in;
   stage_mark(kStTail, st);
-  hipLaunchKernelGGL(sel_tail_kernel, dim3(hc.n_hi), dim3(1024), 0, st, sg, tabH, sel_scores, budgets,
-                     (const unsigned*)hist, state, block_cnt, make_offsets ? offsets : (int64_t*)nullptr,
-                     hc.n_hi, status);
+  if (hc.max_len <= 32768)
+    hipLaunchKernelGGL(sel_tail_kernel<true>, dim3(hc.n_hi), dim3(1024), 0, st, sg, tabH, sel_scores, budgets,
+                       (const unsigned*)hist, state, block_cnt, make_offsets ? offsets : (int64_t*)nullptr,
+                       hc.n_hi, status);
+  else
+    hipLaunchKernelGGL(sel_tail_kernel<false>, dim3(hc.n_hi), dim3(1024), 0, st, sg, tabH, sel_scores, budgets,
+                       (const unsigned*)hist, state, block_cnt, make_offsets ? offsets : (int64_t*)nullptr,
+                       hc.n_hi, status);
   stage_mark(kStEmit, st);
   const int esize = g.f32 ? 4 : 2;
   const int row_bytes = g.head_dim * esize;
