@@ -65,6 +65,8 @@ int validate_config(const lukv_config* cfg, HostCfg* out) {
     if (L > max_len) max_len = (int32_t)L;
   }
   g.total_tokens = out->seq.cu[cfg->n_seqs];
+  // the kernels address one head's keys of one sequence with 32-bit byte offsets
+  if ((int64_t)max_len * cfg->stride_tok * esize >= (1ll << 32)) return LUKV_EINVAL;
   out->max_len = max_len;
   // keys per score workgroup: at most 64 chunks per head (pass B merges them in its prologue)
   g.chunk_keys = 512;

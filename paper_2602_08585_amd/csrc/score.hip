@@ -26,6 +26,8 @@
 // first phase of the budget allocation instead of scoring (it does not depend on scores).
 #include <string.h>
 
+#include <type_traits>
+
 #include "alloc_device.hpp"
 #include "lukv_internal.hpp"
 
@@ -50,6 +52,18 @@ __device__ __forceinline__ f32x16 mma(u32x4 a, u32x4 b, f32x16 c) {
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// Orders the LDS traffic of one wave (its LDS operations execute in order; this keeps the
+// compiler from moving them across) without involving the other waves of the workgroup.
+__device__ __forceinline__ void wave_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+}
+
+template <bool PRIVATE>
+__device__ __forceinline__ void tile_sync() {
+  if constexpr (PRIVATE) wave_sync(); else __syncthreads();
+}
+
 template <bool F32, int D, int RG>
 struct Tile {
   static constexpr int kEsize = F32 ? 4 : 2;
@@ -60,22 +74,28 @@ struct Tile {
   static constexpr int kKeys = 128 / RG;               // keys per tile
   static constexpr int kWaveCols = 4 / RG;             // 32-key subtiles per tile
   static constexpr int kLoads = kKeys * kRowU4 / 256;  // 16-byte loads per thread per tile
-  static constexpr int kRowStep = 256 / kRowU4;        // rows between a thread's loads
+  // With one row group every wave consumes only its own 32 keys of a tile, so it also loads
+  // them itself (64 lanes cover 64/kRowU4 rows per load) and never waits for the other waves;
+  // with several row groups the 256 threads load the shared tile together.
+  static constexpr bool kPrivate = RG == 1;
+  static constexpr int kLoadRowStep = (kPrivate ? 64 : 256) / kRowU4;   // rows between a thread's loads
   static_assert(kLoads >= 1, "tile too small for 256 threads");
+  static_assert(!kPrivate || kLoads * kLoadRowStep == 32, "a wave loads exactly its 32 keys");
 };
 
 // One thread's share of a K tile (plain local arrays: they must stay in registers so that
 // the loads of the next tile are in flight while the current one is consumed).
 // k_issue starts the loads (rows clamped to L-1), k_commit stores them to LDS.
+// `off0` is this thread's byte offset (from the head's first key) of its first row of the
+// tile; the other rows follow at a uniform stride; rows past the sequence clamp to the last.
 template <bool F32, int D, int RG, int NL>
-__device__ __forceinline__ void k_issue(u32x4 (&pre)[NL], const char* base, int64_t tok_bytes,
-                                        int row0, int j0, int L) {
-  using T = Tile<F32, D, RG>;
+__device__ __forceinline__ void k_issue(u32x4 (&pre)[NL], const char* kbase, unsigned off0,
+                                        unsigned row_stride_bytes, unsigned off_last) {
 #pragma unroll
   for (int i = 0; i < NL; ++i) {
-    int j = j0 + row0 + i * T::kRowStep;
-    j = j < L ? j : L - 1;
-    pre[i] = *reinterpret_cast<const u32x4*>(base + (int64_t)j * tok_bytes);
+    unsigned off = off0 + (unsigned)i * row_stride_bytes;
+    off = off < off_last ? off : off_last;
+    pre[i] = *reinterpret_cast<const u32x4*>(kbase + off);
   }
 }
 
@@ -83,28 +103,57 @@ template <bool F32, int D, int RG, int NL>
 __device__ __forceinline__ void k_commit(const u32x4 (&pre)[NL], u32x4* lds, int lds_off) {
   using T = Tile<F32, D, RG>;
 #pragma unroll
-  for (int i = 0; i < NL; ++i) lds[lds_off + i * T::kRowStep * T::kLdsRowU4] = pre[i];
+  for (int i = 0; i < NL; ++i) lds[lds_off + i * T::kLoadRowStep * T::kLdsRowU4] = pre[i];
 }
 
 // Window-query rows of this wave's row blocks, as matrix-core operands held in registers.
+// The workgroup fetches the rows of one row group at a time with coalesced loads (q_fetch),
+// parks them in the K-tile buffer (q_park) and every wave of that group picks its operand
+// layout from there (q_pick): one L2 read per workgroup instead of one per wave.
+template <bool F32, int D, int NBM>
+struct QStage {
+  static constexpr int kEsize = F32 ? 4 : 2;
+  static constexpr int kRowU4 = D * kEsize / 16;
+  static constexpr int kLdsRowU4 = kRowU4 + 1;
+  static constexpr int kRows = 32 * NBM;                 // rows of one row group
+  static constexpr int kLoads = kRows * kRowU4 / 256;    // 16-byte loads per thread
+  static constexpr int kRowStep = 256 / kRowU4;
+};
+
+template <bool F32, int D, int NBM, int NQ>
+__device__ __forceinline__ void q_fetch(u32x4 (&tmp)[NQ], const Geom& g,
+                                        const char* q, int layer, int kvh, int seq, int group) {
+  using QS = QStage<F32, D, NBM>;
+  const int row0 = threadIdx.x / QS::kRowU4, col = threadIdx.x % QS::kRowU4;
+#pragma unroll
+  for (int i = 0; i < QS::kLoads; ++i) {
+    const int lr = row0 + i * QS::kRowStep;                       // row inside the group
+    const int r = 32 * group * g.blocks_per_group + lr;           // row of the head
+    const bool live = lr < 32 * g.blocks_per_group && r < g.rows;
+    const int gq = live ? r / g.window : 0, wi = live ? r % g.window : 0;
+    const char* p = q + ((int64_t)layer * g.qsl + (int64_t)(kvh * g.group + gq) * g.qsh +
+                         (int64_t)(seq * g.window + wi) * g.qst) * QS::kEsize + col * 16;
+    tmp[i] = live ? *reinterpret_cast<const u32x4*>(p) : u32x4{0u, 0u, 0u, 0u};
+  }
+}
+
+template <bool F32, int D, int NBM, int NQ>
+__device__ __forceinline__ void q_park(const u32x4 (&tmp)[NQ], u32x4* lds) {
+  using QS = QStage<F32, D, NBM>;
+  const int row0 = threadIdx.x / QS::kRowU4, col = threadIdx.x % QS::kRowU4;
+#pragma unroll
+  for (int i = 0; i < QS::kLoads; ++i) lds[(row0 + i * QS::kRowStep) * QS::kLdsRowU4 + col] = tmp[i];
+}
+
 template <bool F32, int D, int NBM, int HU>
-__device__ __forceinline__ void load_q(u32x4 (&qreg)[NBM][HU], const Geom& g, const char* q,
-                                       int layer, int kvh, int seq, int blk0, int nb_count,
-                                       int lane) {
-  constexpr int kEsize = F32 ? 4 : 2;
+__device__ __forceinline__ void q_pick(u32x4 (&qreg)[NBM][HU], const u32x4* lds, int lane) {
+  using QS = QStage<F32, D, NBM>;
   const int hf = lane >> 5;
 #pragma unroll
-  for (int nb = 0; nb < NBM; ++nb) {
-    const int r = 32 * (blk0 + nb) + (lane & 31);
-    const bool live = nb < nb_count && r < g.rows;
-    const int gq = live ? r / g.window : 0, i = live ? r % g.window : 0;
-    const char* p = q + ((int64_t)layer * g.qsl + (int64_t)(kvh * g.group + gq) * g.qsh +
-                         (int64_t)(seq * g.window + i) * g.qst) * kEsize +
-                    hf * (D * kEsize / 2);
+  for (int nb = 0; nb < NBM; ++nb)
 #pragma unroll
-    for (int s = 0; s < HU; ++s)
-      qreg[nb][s] = live ? reinterpret_cast<const u32x4*>(p)[s] : u32x4{0u, 0u, 0u, 0u};
-  }
+    for (int s = 0; s < QS::kRowU4 / 2; ++s)
+      qreg[nb][s] = lds[(32 * nb + (lane & 31)) * QS::kLdsRowU4 + hf * (QS::kRowU4 / 2) + s];
 }
 
 __device__ __forceinline__ void merge_stats(float& m, float& z, float m2, float z2, float a) {
@@ -116,11 +165,12 @@ __device__ __forceinline__ void merge_stats(float& m, float& z, float m2, float 
 
 // ---- pass A: softmax statistics ----------------------------------------------------------
 template <bool F32, int D, int NBM, int RG>
-__global__ __launch_bounds__(256) void score_stats_kernel(Geom g, SeqTab tab, const char* q,
+__global__ __launch_bounds__(256, (F32 && D == 128) ? 1 : 2) void score_stats_kernel(Geom g, SeqTab tab, const char* q,
                                                           const char* k, float2* partial,
                                                           int max_chunks, int rows_padded) {
   using T = Tile<F32, D, RG>;
-  __shared__ u32x4 ktile[T::kKeys * T::kLdsRowU4];
+  constexpr int kBufRows = T::kKeys > 32 * NBM ? T::kKeys : 32 * NBM;   // K tile or one Q row group
+  __shared__ u32x4 ktile[kBufRows * T::kLdsRowU4];
   __shared__ float2 wstat[4][NBM][32];
 
   int seq, ch;
@@ -139,15 +189,30 @@ __global__ __launch_bounds__(256) void score_stats_kernel(Geom g, SeqTab tab, co
   const char* kbase = k + ((int64_t)layer * g.sl + (int64_t)kvh * g.sh + (int64_t)tok0 * g.st) * T::kEsize;
   const int j_begin = ch * g.chunk_keys;
   const int j_end = min(L, j_begin + g.chunk_keys);
-  const int64_t tok_bytes = g.st * T::kEsize;
-  const int ld_row0 = threadIdx.x / T::kRowU4, ld_col = threadIdx.x % T::kRowU4;
+  // byte offsets inside one head's keys fit 32 bits (checked on the host)
+  const unsigned tok_bytes = (unsigned)(g.st * T::kEsize);
+  const int ld_row0 = T::kPrivate ? 32 * (int)(threadIdx.x >> 6) + (int)(threadIdx.x & 63) / T::kRowU4
+                                  : (int)threadIdx.x / T::kRowU4;
+  const int ld_col = threadIdx.x % T::kRowU4;
   const int ld_lds = ld_row0 * T::kLdsRowU4 + ld_col;
-  const char* ld_base = kbase + ld_col * 16;
+  const unsigned ld_stride = (unsigned)T::kLoadRowStep * tok_bytes, ld_tile = (unsigned)T::kKeys * tok_bytes;
+  const unsigned ld_last = (unsigned)(L - 1) * tok_bytes + (unsigned)ld_col * 16u;
+  unsigned ld_off = (unsigned)(j_begin + ld_row0) * tok_bytes + (unsigned)ld_col * 16u;
   u32x4 pre[T::kLoads];
-  k_issue<F32, D, RG, T::kLoads>(pre, ld_base, tok_bytes, ld_row0, j_begin, L);
+  k_issue<F32, D, RG, T::kLoads>(pre, kbase, ld_off, ld_stride, ld_last);
 
   u32x4 qreg[NBM][T::kHalfU4];
-  load_q<F32, D, NBM, T::kHalfU4>(qreg, g, q, layer, kvh, seq, blk0, nb_count, lane);
+  {
+    u32x4 qtmp[QStage<F32, D, NBM>::kLoads];
+    for (int grp = 0; grp < RG; ++grp) {
+      q_fetch<F32, D, NBM, QStage<F32, D, NBM>::kLoads>(qtmp, g, q, layer, kvh, seq, grp);
+      if (grp) __syncthreads();
+      q_park<F32, D, NBM, QStage<F32, D, NBM>::kLoads>(qtmp, ktile);
+      __syncthreads();
+      if (rg == grp) q_pick<F32, D, NBM, T::kHalfU4>(qreg, ktile, lane);
+    }
+  }
+  __syncthreads();   // the buffer now turns into the K tile
 
   // window row index of this lane's query in every block (for the causal range)
   int wrow[NBM];
@@ -159,43 +224,49 @@ __global__ __launch_bounds__(256) void score_stats_kernel(Geom g, SeqTab tab, co
   for (int nb = 0; nb < NBM; ++nb) { m[nb] = -INFINITY; z[nb] = 0.f; }
 
   for (int j0 = j_begin; j0 < j_end; j0 += T::kKeys) {
-    __syncthreads();               // every wave is done reading the previous tile
+    tile_sync<T::kPrivate>();      // the previous tile has been read
     k_commit<F32, D, RG, T::kLoads>(pre, ktile, ld_lds);
-    __syncthreads();
-    if (j0 + T::kKeys < j_end) k_issue<F32, D, RG, T::kLoads>(pre, ld_base, tok_bytes, ld_row0, j0 + T::kKeys, L);
+    tile_sync<T::kPrivate>();
+    ld_off += ld_tile;
+    if (j0 + T::kKeys < j_end) k_issue<F32, D, RG, T::kLoads>(pre, kbase, ld_off, ld_stride, ld_last);
     const int jw = j0 + 32 * kt;   // first key of this wave's 32-key subtile
     if (jw < j_end) {              // wave-uniform
       u32x4 kreg[T::kHalfU4];
       const u32x4* src = ktile + (32 * kt + (lane & 31)) * T::kLdsRowU4 + hf * T::kHalfU4;
 #pragma unroll
       for (int s = 0; s < T::kHalfU4; ++s) kreg[s] = src[s];
-      const bool need_mask = jw + 32 > P;
+      // Only the last tiles of a sequence reach into the observation window (causal range) or
+      // past the end; every other tile takes the branch-free path.
+      auto fold = [&](auto masked_tag) {
+        constexpr bool kMasked = decltype(masked_tag)::value;
 #pragma unroll
-      for (int nb = 0; nb < NBM; ++nb) {
-        if (nb < nb_count) {
-          f32x16 acc = {0};
+        for (int nb = 0; nb < NBM; ++nb) {
+          if (nb < nb_count) {
+            f32x16 acc = {0};
 #pragma unroll
-          for (int s = 0; s < T::kHalfU4; ++s) acc = mma<F32>(kreg[s], qreg[nb][s], acc);
-          if (need_mask) {
+            for (int s = 0; s < T::kHalfU4; ++s) acc = mma<F32>(kreg[s], qreg[nb][s], acc);
+            if constexpr (kMasked) {
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-              const int j = jw + 8 * (v >> 2) + 4 * hf + (v & 3);
-              if (j >= L || j > P + wrow[nb]) acc[v] = -INFINITY;
+              for (int v = 0; v < 16; ++v) {
+                const int j = jw + 8 * (v >> 2) + 4 * hf + (v & 3);
+                if (j >= L || j > P + wrow[nb]) acc[v] = -INFINITY;
+              }
             }
+            float tm = acc[0];
+#pragma unroll
+            for (int v = 1; v < 16; ++v) tm = fmaxf(tm, acc[v]);
+            const float mn = fmaxf(m[nb], tm);
+            const float ms = mn == -INFINITY ? 0.f : mn;
+            float zz = z[nb] * fast_exp2((m[nb] - ms) * a);
+            const float off = -ms * a;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) zz += fast_exp2(fmaf(acc[v], a, off));
+            z[nb] = zz;
+            m[nb] = mn;
           }
-          float tm = acc[0];
-#pragma unroll
-          for (int v = 1; v < 16; ++v) tm = fmaxf(tm, acc[v]);
-          const float mn = fmaxf(m[nb], tm);
-          const float ms = mn == -INFINITY ? 0.f : mn;
-          float zz = z[nb] * fast_exp2((m[nb] - ms) * a);
-          const float off = -ms * a;
-#pragma unroll
-          for (int v = 0; v < 16; ++v) zz += fast_exp2(fmaf(acc[v], a, off));
-          z[nb] = zz;
-          m[nb] = mn;
         }
-      }
+      };
+      if (jw + 32 > P) fold(std::true_type{}); else fold(std::false_type{});
     }
   }
 
@@ -221,14 +292,15 @@ __global__ __launch_bounds__(256) void score_stats_kernel(Geom g, SeqTab tab, co
 
 // ---- pass B: normalised window sums ------------------------------------------------------
 template <bool F32, int D, int NBM, int RG>
-__global__ __launch_bounds__(256) void score_accum_kernel(Geom g, SeqTab tab, AllocIO aio,
+__global__ __launch_bounds__(256, (F32 && D == 128) ? 1 : 2) void score_accum_kernel(Geom g, SeqTab tab, AllocIO aio,
                                                           int n_alloc_blocks, int alloc_bpp,
                                                           const char* q,
                                                           const char* k, const float2* partial,
                                                           float* raw, int max_chunks,
                                                           int rows_padded) {
   using T = Tile<F32, D, RG>;
-  __shared__ u32x4 ktile[T::kKeys * T::kLdsRowU4];
+  constexpr int kBufRows = T::kKeys > 32 * NBM ? T::kKeys : 32 * NBM;   // K tile or one Q row group
+  __shared__ u32x4 ktile[kBufRows * T::kLdsRowU4];
   __shared__ __align__(16) float rowc_s[kMaxRows];
   __shared__ float2 pm[kMaxRows];
   __shared__ float colred[4][32];
@@ -255,16 +327,26 @@ __global__ __launch_bounds__(256) void score_accum_kernel(Geom g, SeqTab tab, Al
   const char* kbase = k + ((int64_t)layer * g.sl + (int64_t)kvh * g.sh + (int64_t)tok0 * g.st) * T::kEsize;
   const int j_begin = ch * g.chunk_keys;
   const int j_end = min(P, j_begin + g.chunk_keys);
-  const int64_t tok_bytes = g.st * T::kEsize;
-  const int ld_row0 = threadIdx.x / T::kRowU4, ld_col = threadIdx.x % T::kRowU4;
+  // byte offsets inside one head's keys fit 32 bits (checked on the host)
+  const unsigned tok_bytes = (unsigned)(g.st * T::kEsize);
+  const int ld_row0 = T::kPrivate ? 32 * (int)(threadIdx.x >> 6) + (int)(threadIdx.x & 63) / T::kRowU4
+                                  : (int)threadIdx.x / T::kRowU4;
+  const int ld_col = threadIdx.x % T::kRowU4;
   const int ld_lds = ld_row0 * T::kLdsRowU4 + ld_col;
-  const char* ld_base = kbase + ld_col * 16;
+  const unsigned ld_stride = (unsigned)T::kLoadRowStep * tok_bytes, ld_tile = (unsigned)T::kKeys * tok_bytes;
+  const unsigned ld_last = (unsigned)(L - 1) * tok_bytes + (unsigned)ld_col * 16u;
+  unsigned ld_off = (unsigned)(j_begin + ld_row0) * tok_bytes + (unsigned)ld_col * 16u;
   u32x4 pre[T::kLoads];
-  k_issue<F32, D, RG, T::kLoads>(pre, ld_base, tok_bytes, ld_row0, j_begin, L);
+  k_issue<F32, D, RG, T::kLoads>(pre, kbase, ld_off, ld_stride, ld_last);
+
+  // window queries of the first row group: in flight together with the K tile above and the
+  // per-chunk statistics below
+  u32x4 qtmp[QStage<F32, D, NBM>::kLoads];
+  q_fetch<F32, D, NBM, QStage<F32, D, NBM>::kLoads>(qtmp, g, q, layer, kvh, seq, 0);
 
   // Softmax constant of every window row: merge the (max, sum) pairs that pass A left per
-  // chunk of this head, c_r = max_r * a + log2(sum_r).  Each thread first folds a share of
-  // the chunks of one row (loads in batches of eight), LDS joins the shares.
+  // chunk of this head, c_r = max_r * a + log2(sum_r).  Each thread folds a share of the
+  // chunks of one row, 16 pairs in flight at once; LDS joins the shares.
   {
     const int n_chunks = (L + g.chunk_keys - 1) / g.chunk_keys;   // chunks pass A used
     const int nparts = rows_padded >= 256 ? 1 : 256 / rows_padded;
@@ -274,13 +356,19 @@ __global__ __launch_bounds__(256) void score_accum_kernel(Geom g, SeqTab tab, Al
       const int r = item % rows_padded, part = item / rows_padded;
       const int c_end = min(n_chunks, (part + 1) * cpp);
       float mm = -INFINITY, zz = 0.f;
-      for (int c0 = part * cpp; c0 < c_end; c0 += 8) {
-        float2 st[8];
+      for (int c0 = part * cpp; c0 < c_end; c0 += 16) {
+        float2 st[16];
 #pragma unroll
-        for (int u = 0; u < 8; ++u)
+        for (int u = 0; u < 16; ++u)
           st[u] = c0 + u < c_end ? hp[(int64_t)(c0 + u) * rows_padded + r] : make_float2(-INFINITY, 0.f);
+        float rm = -INFINITY;
 #pragma unroll
-        for (int u = 0; u < 8; ++u) merge_stats(mm, zz, st[u].x, st[u].y, a);
+        for (int u = 0; u < 16; ++u) rm = fmaxf(rm, st[u].x);
+        const float rms = rm == -INFINITY ? 0.f : rm;
+        float rz = 0.f;
+#pragma unroll
+        for (int u = 0; u < 16; ++u) rz = fmaf(st[u].y, fast_exp2((st[u].x - rms) * a), rz);
+        merge_stats(mm, zz, rm, rz, a);
       }
       if (nparts == 1) rowc_s[r] = r < g.rows ? mm * a + log2f(zz) : INFINITY;
       else pm[part * rows_padded + r] = make_float2(mm, zz);
@@ -301,15 +389,25 @@ __global__ __launch_bounds__(256) void score_accum_kernel(Geom g, SeqTab tab, Al
   }
 
   u32x4 qreg[NBM][T::kHalfU4];
-  load_q<F32, D, NBM, T::kHalfU4>(qreg, g, q, layer, kvh, seq, blk0, nb_count, lane);
+  for (int grp = 0; grp < RG; ++grp) {
+    if (grp) {
+      q_fetch<F32, D, NBM, QStage<F32, D, NBM>::kLoads>(qtmp, g, q, layer, kvh, seq, grp);
+      __syncthreads();
+    }
+    q_park<F32, D, NBM, QStage<F32, D, NBM>::kLoads>(qtmp, ktile);
+    __syncthreads();
+    if (rg == grp) q_pick<F32, D, NBM, T::kHalfU4>(qreg, ktile, lane);
+  }
+  __syncthreads();   // the buffer now turns into the K tile; rowc_s is complete
 
   float* out = raw + ((int64_t)layer * g.n_kv_heads + kvh) * g.total_tokens + tok0;
 
   for (int j0 = j_begin; j0 < j_end; j0 += T::kKeys) {
-    __syncthreads();
+    tile_sync<T::kPrivate>();
     k_commit<F32, D, RG, T::kLoads>(pre, ktile, ld_lds);
-    __syncthreads();
-    if (j0 + T::kKeys < j_end) k_issue<F32, D, RG, T::kLoads>(pre, ld_base, tok_bytes, ld_row0, j0 + T::kKeys, L);
+    tile_sync<T::kPrivate>();
+    ld_off += ld_tile;
+    if (j0 + T::kKeys < j_end) k_issue<F32, D, RG, T::kLoads>(pre, kbase, ld_off, ld_stride, ld_last);
     const int jw = j0 + 32 * kt;
     float col = 0.f;
     if (jw < j_end) {
