@@ -9,7 +9,7 @@
 // find the gain g* at which the cumulated units (largest gain first) reach the remaining
 // budget, give every head all its units above g*, and hand the units at exactly g* out in
 // head order.
-//   phase A: hull vertices by their definition, four threads per (head, knot): knot g is a
+//   phase A: hull vertices by their definition, sixteen threads per (head, knot): knot g is a
 //            vertex of the upper concave hull iff every chord from an earlier knot to g is
 //            strictly steeper than every chord from g to a later knot (end knots always
 //            are).  All chords are independent fp64 divisions: no serial chain, any number
@@ -45,7 +45,7 @@ struct AllocIO {
   int64_t B[LUKV_MAX_SEQS];
 };
 
-constexpr int kAllocPartsPerKnot = 4;   // threads sharing the chords of one knot in phase A
+constexpr int kAllocPartsPerKnot = 16;  // threads sharing the chords of one knot in phase A
 
 __host__ __device__ inline int alloc_blocks_a(int n_heads, int n_grid) {
   return (n_heads * n_grid * kAllocPartsPerKnot + 255) / 256;   // 256-thread blocks per problem
@@ -156,14 +156,19 @@ __device__ inline void alloc_phase_b(const AllocIO& io, int p, char* lds, int ld
   const int32_t* kn = io.knots + hbase * Gp;
   const float* cu = io.curves + hbase * Gp;
 
-  // LDS plan (small problems): flags/knots/curves [nseg] + segment key/weight [nseg] + per-head
-  // gt/eq sums [NH]
-  const bool small = nseg <= 1024 && NH <= 1024 && lds_bytes >= 4096 + 1024 * 24 + 1024 * 4;
-  int32_t* l_kn = reinterpret_cast<int32_t*>(lds + 4096);
-  float* l_cu = reinterpret_cast<float*>(lds + 4096 + nseg * 4);
-  unsigned* l_w = reinterpret_cast<unsigned*>(lds + 4096 + nseg * 8);
-  unsigned long long* l_key = reinterpret_cast<unsigned long long*>(lds + 4096 + (nseg * 12 + 7) / 8 * 8);
-  unsigned* l_vtx = reinterpret_cast<unsigned*>(lds + 4096 + (nseg * 12 + 7) / 8 * 8 + nseg * 8);
+  // LDS plan (small problems, <= 1024 segments and <= 64 heads): vertex bit masks, per-head
+  // bounds and sums, knots, curves and the segments themselves all live in LDS
+  const int words = (Gp + 63) / 64;                      // mask words per head
+  const bool small = nseg <= 1024 && NH <= 64 && NH * words <= 96 && lds_bytes >= 32768;
+  unsigned long long* l_mask = reinterpret_cast<unsigned long long*>(lds + 3328);   // [NH][words]
+  int32_t* l_lb = reinterpret_cast<int32_t*>(lds + 4096);                           // b_min per head
+  int32_t* l_cp = l_lb + 64;                                                        // cap per head
+  long long* h_gt = reinterpret_cast<long long*>(lds + 4608);                       // per-head sums
+  long long* h_eq = h_gt + 64;
+  int32_t* l_kn = reinterpret_cast<int32_t*>(lds + 5632);
+  float* l_cu = reinterpret_cast<float*>(lds + 5632 + nseg * 4);
+  unsigned* l_w = reinterpret_cast<unsigned*>(lds + 5632 + nseg * 8);
+  unsigned long long* l_key = reinterpret_cast<unsigned long long*>(lds + 5632 + (nseg * 12 + 7) / 8 * 8);
   unsigned long long* skey = small ? l_key : io.seg_key + hbase * Gp;
   unsigned* sw = small ? l_w : io.seg_w + hbase * Gp;
   __syncthreads();
@@ -171,8 +176,22 @@ __device__ inline void alloc_phase_b(const AllocIO& io, int p, char* lds, int ld
     red[0] = red[1] = red[2] = 0;
     sel[0] = 0ull; sel[1] = 0ull; sel[2] = ~0ull; sel[3] = 0ull;
   }
-  if (small)
-    for (int i = t; i < (int)nseg; i += nt) { l_vtx[i] = (unsigned)vtx[i]; l_kn[i] = kn[i]; l_cu[i] = cu[i]; }
+  if (small) {
+    for (int i = t; i < NH * words; i += nt) l_mask[i] = 0ull;
+    for (int h = t; h < NH; h += nt) {
+      l_lb[h] = io.b_min[hbase + h];
+      const int32_t last = kn[(int64_t)h * Gp + Gp - 1], bm = io.b_max[hbase + h];
+      l_cp[h] = bm < last ? bm : last;
+      h_gt[h] = 0;
+      h_eq[h] = 0;
+    }
+    __syncthreads();
+    for (int i = t; i < (int)nseg; i += nt) {
+      l_kn[i] = kn[i];
+      l_cu[i] = cu[i];
+      if (vtx[i]) { const int h = i / Gp, g = i - h * Gp; atomicOr(&l_mask[h * words + (g >> 6)], 1ull << (g & 63)); }
+    }
+  }
   __syncthreads();
 
   // one segment per vertex (to the next vertex), clipped to (b_min, cap]
@@ -181,18 +200,30 @@ __device__ inline void alloc_phase_b(const AllocIO& io, int p, char* lds, int ld
   for (int64_t i = t; i < nseg; i += nt) {
     const int h = (int)(i / Gp), g = (int)(i - (int64_t)h * Gp);
     const int64_t hb = (int64_t)h * Gp;
-    const long long lb = io.b_min[hbase + h];
-    const long long cp = min((long long)io.b_max[hbase + h], (long long)(small ? l_kn[hb + Gp - 1] : kn[hb + Gp - 1]));
+    const long long lb = small ? l_lb[h] : io.b_min[hbase + h];
+    const long long cp = small ? l_cp[h] : min((long long)io.b_max[hbase + h], (long long)kn[hb + Gp - 1]);
     if (g == 0) {
       if (lb < 0 || lb > cp) bad = 1;
       sum_min += lb;
     }
     unsigned w = 0;
     unsigned long long key = 0;
-    if (g < Gp - 1 && (small ? l_vtx[i] != 0u : vtx[i] != 0)) {
-      int c = g + 1;   // next vertex; the last knot is always one
-      if (small) { while (c < Gp - 1 && !l_vtx[hb + c]) ++c; }
-      else { while (c < Gp - 1 && !vtx[hb + c]) ++c; }
+    bool is_vertex;
+    int c = g + 1;   // next vertex; the last knot is always one
+    if (small) {
+      const unsigned long long* mk = l_mask + h * words;
+      is_vertex = (mk[g >> 6] >> (g & 63)) & 1ull;
+      if (is_vertex && g < Gp - 1) {
+        int wd = c >> 6;
+        unsigned long long m = mk[wd] & (~0ull << (c & 63));
+        while (m == 0ull && wd + 1 < words) m = mk[++wd];
+        c = m ? wd * 64 + __ffsll((long long)m) - 1 : Gp - 1;
+      }
+    } else {
+      is_vertex = vtx[i] != 0;
+      if (is_vertex) while (c < Gp - 1 && !vtx[hb + c]) ++c;
+    }
+    if (g < Gp - 1 && is_vertex) {
       const long long na = small ? l_kn[i] : kn[i], nb = small ? l_kn[hb + c] : kn[hb + c];
       const double ua = (double)(small ? l_cu[i] : cu[i]), ub = (double)(small ? l_cu[hb + c] : cu[hb + c]);
       const long long lo = max(na, lb), hi = min(nb, cp);
@@ -304,12 +335,8 @@ __device__ inline void alloc_phase_b(const AllocIO& io, int p, char* lds, int ld
   const long long rem = active ? (long long)sel[1] : 0;
 
   // budgets: everything above g*, ties at g* in head order
-  long long* h_gt = reinterpret_cast<long long*>(l_vtx);   // flags are dead by now: reuse for per-head sums
-  long long* h_eq = h_gt + NH;
-  const bool head_lds = small && (int64_t)NH * 16 <= nseg * 4;
+  const bool head_lds = small;
   if (head_lds) {
-    for (int h = t; h < NH; h += nt) { h_gt[h] = 0; h_eq[h] = 0; }
-    __syncthreads();
     if (active) {
       for (int i = t; i < (int)nseg; i += nt) {
         const unsigned w = sw[i];
