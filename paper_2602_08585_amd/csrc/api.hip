@@ -1,6 +1,5 @@
 // C ABI of liblukv: argument checks, workspace layout, and the order of launches.
 #include <math.h>
-#include <stdlib.h>
 #include <string.h>
 
 #include "alloc_device.hpp"
@@ -71,8 +70,6 @@ int validate_config(const lukv_config* cfg, HostCfg* out) {
   // keys per score workgroup: at most 64 chunks per head (pass B merges them in its prologue)
   g.chunk_keys = 512;
   while ((max_len + g.chunk_keys - 1) / g.chunk_keys > 64) g.chunk_keys *= 2;
-  if (const char* e = getenv("LUKV_TUNE_CHUNK")) { const int c = atoi(e); if (c >= 128 && c % 128 == 0 && (max_len + c - 1) / c <= 64) g.chunk_keys = c; }
-  if (const char* e = getenv("LUKV_TUNE_RG")) { const int r = atoi(e); if ((r == 2 || r == 4) && r >= g.row_groups) { g.row_groups = r; g.blocks_per_group = (g.row_blocks + r - 1) / r; } }
   out->n_hi = cfg->n_seqs * g.n_layers * g.n_kv_heads;
   return LUKV_OK;
 }

@@ -50,6 +50,8 @@ def test_handworked_budgets_all_B():
         assert st == 0 and b.tolist() == [int(t) for t in want.split(",")]
     b, st = O.allocate(U, knots, np.ones(2, np.int32), four, 3)
     assert st == 0 and b.tolist() == [int(t) for t in g["bmin11_B3"][0].split(",")]
+    b, st = O.allocate(U, knots, np.array([0, 3], np.int32), four, 4)
+    assert st == 0 and b.tolist() == [int(t) for t in g["bmin03_B4"][0].split(",")]
 
 
 def test_infeasible_budgets_flagged():
@@ -85,6 +87,17 @@ def test_vertex_definition_equals_monotone_chain(seed):
     U = np.cumsum(inc).astype(np.float32)
     knots = ((np.arange(Gp) * L) // (Gp - 1)).astype(np.int32) if Gp > 1 else np.zeros(1, np.int32)
     assert O.concave_hull(knots, U) == _monotone_chain(knots, U)
+
+
+def test_collinear_knots_are_not_vertices():
+    # slopes 2, 2, 1, 1, 0 by hand: only the knots where the slope drops are vertices
+    knots = np.arange(6, dtype=np.int32)
+    U = np.array([0, 2, 4, 5, 6, 6], dtype=np.float32)
+    assert O.concave_hull(knots, U) == [0, 2, 4, 5]
+    assert O.marginal_gains(knots, U) == [(0, 2, 2.0), (2, 4, 1.0), (4, 5, 0.0)]
+    assert _monotone_chain(knots, U) == [0, 2, 4, 5]
+    # a straight line has only its end points
+    assert O.concave_hull(knots, np.arange(6, dtype=np.float32)) == [0, 5]
 
 
 # --- unit-level PAVA (textbook pool-adjacent-violators on the marginal decreases) ----------

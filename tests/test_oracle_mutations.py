@@ -1,0 +1,92 @@
+"""The pins must bite: plant one plausible mistake at a time in a private copy of the
+oracle's source (CPU only), swap it in, and check that a named pin fails.
+
+The mutated copy is built by replacing one snippet of the oracle's text; each snippet
+must occur exactly once, so a change to the oracle that makes a mutant meaningless
+breaks this file loudly instead of silently weakening it.
+"""
+import inspect
+import types
+
+import pytest
+
+from oracle import lukv_oracle as O
+from tests import test_oracle_allocate as TA
+from tests import test_oracle_score as TS
+
+PUBLIC = ["window_attention_sum", "max_pool_1d", "score", "concave_hull", "marginal_gains",
+          "_gain_of_unit", "_slope", "allocate", "select", "compact", "offsets_of"]
+
+MUTANTS = {
+    # name: (snippet, replacement, pin that must fail)
+    "dropped_group_mean": ("out[c] = acc / G", "out[c] = acc",
+                           lambda: TS.test_identical_keys_closed_form_and_group_mean()),
+    "non_causal_window": ("visible = j <= t ", "visible = j <= L ",
+                          lambda: TS.test_handworked_unpooled_is_causal()),
+    "strictly_causal_window": ("visible = j <= t ", "visible = j < t ",
+                               lambda: TS.test_identical_keys_closed_form_and_group_mean()),
+    "mean_over_window": ("acc += p.sum(axis=0)", "acc += p.mean(axis=0)",
+                         lambda: TS.test_total_mass_is_window_size()),
+    "missing_scale": ("scale = 1.0 / math.sqrt(d)", "scale = 1.0",
+                      lambda: TS.test_brute_force_definition()),
+    "softmax_over_queries": ("p = e / e.sum(axis=1, keepdims=True)",
+                             "p = e / e.sum(axis=0, keepdims=True)",
+                             lambda: TS.test_total_mass_is_window_size()),
+    "pool_window_shifted": ("out = np.maximum(out, padded[..., t:t + n])",
+                            "out = np.maximum(out, padded[..., t + 1:t + 1 + n] if t + 1 + n <= "
+                            "padded.shape[-1] else out)",
+                            lambda: TS.test_pool_properties_and_library_cross_check()),
+    "pool_over_window_too": ("s[:, :P] = max_pool_1d(r[:, :P], pool_kernel)",
+                             "s[:, :P] = max_pool_1d(r, pool_kernel)[:, :P]",
+                             lambda: TS.test_handworked_pool_stays_inside_prefix()),
+    "sink_not_forced": ("s[:, :min(n_sink, L)] = np.inf", "pass",
+                        lambda: TS.test_brute_force_definition()),
+    "hull_keeps_collinear": ("if steepness_in > steepness_out:", "if steepness_in >= steepness_out:",
+                             lambda: TA.test_collinear_knots_are_not_vertices()),
+    "hull_local_only": ("steepness_in = chord[:g, g].min()", "steepness_in = chord[g - 1, g]",
+                        lambda: TA.test_vertex_definition_equals_monotone_chain(0)),
+    "segment_owner_off_by_one": ("if lo < u <= hi:", "if lo <= u < hi:",
+                                 lambda: TA.test_handworked_hull_and_gains()),
+    "head_tie_highest_first": ("h = int(np.argmax(nxt)) ", "h = int(len(nxt) - 1 - np.argmax(nxt[::-1])) ",
+                               lambda: TA.test_handworked_budgets_all_B()),
+    "min_retention_ignored": ("budgets = np.array([int(x) for x in b_min], dtype=np.int64)",
+                              "budgets = np.array([0 for x in b_min], dtype=np.int64)",
+                              lambda: TA.test_handworked_budgets_all_B()),
+    "topk_ties_unstable_order": ('order = np.argsort(-s.astype(np.float64), kind="stable")',
+                                 'order = np.argsort(-s.astype(np.float64)[::-1], kind="stable")[::1]; '
+                                 'order = len(s) - 1 - order',
+                                 lambda: TS.test_handworked_topk_lowest_index_ties()),
+    "topk_smallest": ('order = np.argsort(-s.astype(np.float64), kind="stable")',
+                      'order = np.argsort(s.astype(np.float64), kind="stable")',
+                      lambda: TA.test_select_brute_force_with_ties(0)),
+    "chord_transposed": ("chord = (u[None, :] - u[:, None]) / (n[None, :] - n[:, None])",
+                         "chord = ((u[None, :] - u[:, None]) / (n[None, :] - n[:, None])).T * -1",
+                         lambda: TA.test_handworked_hull_and_gains()),
+}
+
+
+def _mutated_module(snippet, replacement):
+    src = inspect.getsource(O)
+    assert src.count(snippet) == 1, "mutation target must occur exactly once: %r" % snippet
+    mod = types.ModuleType("lukv_oracle_mutant")
+    exec(compile(src.replace(snippet, replacement), "lukv_oracle_mutant", "exec"), mod.__dict__)
+    return mod
+
+
+@pytest.mark.parametrize("name", sorted(MUTANTS))
+def test_planted_mistake_is_caught(name, monkeypatch):
+    snippet, replacement, pin = MUTANTS[name]
+    mutant = _mutated_module(snippet, replacement)
+    for fn in PUBLIC:
+        monkeypatch.setattr(O, fn, getattr(mutant, fn))
+    with pytest.raises(AssertionError):
+        pin()
+
+
+def test_unmutated_copy_passes_the_same_pins(monkeypatch):
+    """Control: the swap mechanism itself does not make pins fail."""
+    clean = _mutated_module("out[c] = acc / G", "out[c] = acc / G ")
+    for fn in PUBLIC:
+        monkeypatch.setattr(O, fn, getattr(clean, fn))
+    for _, _, pin in MUTANTS.values():
+        pin()

@@ -54,6 +54,15 @@ def test_handworked_pooled(p, key):
     assert np.array_equal(s[0][fin], want[fin].astype(np.float32))
 
 
+def test_handworked_pool_stays_inside_prefix():
+    g = _golden()
+    k = np.log(np.array(g["a2"]))[None, :, None]
+    s = O.score(np.ones((1, 2, 1)), k, 1, window=2, pool_kernel=3, n_sink=0, scale=1.0)
+    want = np.array(g["pool3_a2"])
+    assert np.array_equal(np.isinf(s[0]), np.isinf(want))
+    assert np.array_equal(s[0][:4], want[:4].astype(np.float32))
+
+
 def test_handworked_topk_lowest_index_ties():
     g, q, k = _handworked_inputs()
     s = O.score(q, k, 1, window=2, pool_kernel=3, n_sink=0, scale=1.0)
