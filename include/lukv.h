@@ -25,8 +25,9 @@
  *     [cu_seqlens[s], cu_seqlens[s+1]) and window-query rows [s*window, (s+1)*window).
  *   - Limits: 1 <= n_seqs <= LUKV_MAX_SEQS; head_dim in {64, 128}; (n_q_heads/n_kv_heads)*window
  *     <= 512 (<= 256 for f32 with head_dim 128); pool_kernel odd, 1..31; every sequence longer
- *     than `window` and n_sink <= L - window; at most 2^31-1 packed tokens; one sequence's keys
- *     of one head span less than 4 GiB (L * stride_tok * element size < 2^32).
+ *     than `window`, at most 1 048 576 tokens long, and n_sink <= L - window; at most 2^31-1
+ *     packed tokens; one sequence's keys of one head span less than 4 GiB
+ *     (L * stride_tok * element size < 2^32).
  */
 #ifndef LUKV_H
 #define LUKV_H

@@ -58,7 +58,7 @@ int validate_config(const lukv_config* cfg, HostCfg* out) {
   for (int s = 0; s < cfg->n_seqs; ++s) {
     const int64_t a = cfg->cu_seqlens[s], b = cfg->cu_seqlens[s + 1];
     const int64_t L = b - a;
-    if (L <= g.window || g.n_sink > L - g.window) return LUKV_EINVAL;
+    if (L <= g.window || g.n_sink > L - g.window || L > kMaxSeqLen) return LUKV_EINVAL;
     out->seq.cu[s] = (int32_t)a;
     out->seq.cu[s + 1] = (int32_t)b;
     if (L > max_len) max_len = (int32_t)L;
@@ -90,8 +90,8 @@ WsLayout make_layout(const HostCfg& hc, int32_t n_grid, bool alloc_only) {
   const Geom& g = hc.g;
   w.n_hi = hc.n_hi;
   w.max_chunks = g.chunk_keys > 0 ? (hc.max_len + g.chunk_keys - 1) / g.chunk_keys : 0;
-  w.max_blocks = (hc.max_len + kEmitElems - 1) / kEmitElems;
   w.max_slices = (hc.max_len + kSliceElems - 1) / kSliceElems;
+  w.range_stride = w.max_chunks * 4 > w.max_slices ? w.max_chunks * 4 : w.max_slices;
   w.rows_padded = g.row_blocks * 32;
   int64_t off = 0;
   auto take = [&](int64_t bytes) { const int64_t o = off; off = align_up(off + bytes, 256); return o; };
@@ -102,7 +102,11 @@ WsLayout make_layout(const HostCfg& hc, int32_t n_grid, bool alloc_only) {
   w.raw = take(score_bytes);
   w.pooled = take(score_bytes);
   w.sel_state = take(n_sel * 16);
-  w.slice_cnt = take(n_sel * w.max_blocks * 8);
+  w.slice_cnt = take(n_sel * w.max_slices * 8);
+  w.range = take(n_sel * w.range_stride * 8);
+  w.head_dig = take(n_sel * 8);
+  w.by_bin = take(alloc_only ? 0 : score_bytes * 2);
+  w.cand = take(alloc_only ? 0 : score_bytes * 2);
   const int64_t nseg = (int64_t)hc.n_hi * (n_grid > 0 ? n_grid : 0);
   w.alloc_vertex = take(nseg * 4);
   w.seg_key = take(nseg * 8);

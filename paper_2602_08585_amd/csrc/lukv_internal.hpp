@@ -14,8 +14,8 @@ typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 
 // ---- tiling constants -------------------------------------------------------------------
 constexpr int kSliceElems = 1024;  // scores one workgroup of the selection histogram owns
-constexpr int kEmitElems = 256;    // scores one workgroup of the emit/gather kernel owns
-constexpr int kHistBins = 2048;    // bins of the widest radix digit (11, 11, 10 bits)
+constexpr int kHistBins = 2048;    // bins of the widest radix digit (11 bits)
+constexpr int kMaxSeqLen = 1 << 20;  // tokens per sequence (1024 slices: one selection thread per slice)
 constexpr int kMaxGrid = 1980;     // utility-curve grid points (hull stack lives in LDS)
 constexpr int kMaxRows = 512;      // G * window upper bound
 
@@ -46,16 +46,20 @@ struct Geom {
 // Byte offsets into the caller's workspace.
 struct WsLayout {
   int64_t alloc_vertex;          // i32 [n_problems * n_heads * n_grid]
-  int64_t hist;                  // u32 [n_hi * max_slices * kHistBins / 2] packed 16-bit counts
+  int64_t hist;                  // u32 [n_hi * max_slices * kHistBins / 2] packed 16-bit suffix counts
+  int64_t range;                 // float2 [n_hi * range_stride] (min, max) of the metric per chunk part
+  int64_t head_dig;              // uint2 [n_hi] first digit of the selection: (base key, shift)
+  int64_t by_bin;                // u64 [n_layers * n_kv_heads * total_tokens] (key, position) by slice and bin
+  int64_t cand;                  // u64, same shape: threshold candidates of a head beyond the LDS list
   int64_t partial;               // float2 [n_hi * max_chunks * rows_padded]
   int64_t raw;                   // float [n_layers * n_kv_heads * total_tokens]
   int64_t pooled;                // float, same shape
   int64_t sel_state;             // uint4 [n_hi]
-  int64_t slice_cnt;             // uint2 [n_hi * max_blocks]
+  int64_t slice_cnt;             // uint2 [n_hi * max_slices] kept rows / ties before each slice
   int64_t seg_key;               // u64 [n_problems * n_heads * n_grid]
   int64_t seg_w;                 // u32 [n_problems * n_heads * n_grid]
   int64_t total;
-  int32_t n_hi, max_chunks, max_slices, max_blocks, rows_padded;
+  int32_t n_hi, max_chunks, max_slices, range_stride, rows_padded;
 };
 
 struct HostCfg {

@@ -296,7 +296,7 @@ __global__ __launch_bounds__(256, (F32 && D == 128) ? 1 : 2) void score_accum_ke
                                                           int n_alloc_blocks, int alloc_bpp,
                                                           const char* q,
                                                           const char* k, const float2* partial,
-                                                          float* raw, int max_chunks,
+                                                          float* raw, float2* range, int max_chunks,
                                                           int rows_padded) {
   using T = Tile<F32, D, RG>;
   constexpr int kBufRows = T::kKeys > 32 * NBM ? T::kKeys : 32 * NBM;   // K tile or one Q row group
@@ -401,6 +401,7 @@ __global__ __launch_bounds__(256, (F32 && D == 128) ? 1 : 2) void score_accum_ke
   __syncthreads();   // the buffer now turns into the K tile; rowc_s is complete
 
   float* out = raw + ((int64_t)layer * g.n_kv_heads + kvh) * g.total_tokens + tok0;
+  float vmin = INFINITY, vmax = -INFINITY;   // range of the values this lane writes
 
   for (int j0 = j_begin; j0 < j_end; j0 += T::kKeys) {
     tile_sync<T::kPrivate>();
@@ -441,8 +442,21 @@ __global__ __launch_bounds__(256, (F32 && D == 128) ? 1 : 2) void score_accum_ke
         for (int t = 1; t < RG; ++t) col += colred[t * n_kt + kt][lane & 31];
       }
     }
-    if (rg == 0 && lane < 32 && jw + lane < j_end) out[jw + lane] = col * g.inv_group;
+    if (rg == 0 && lane < 32 && jw + lane < j_end) {
+      const float val = col * g.inv_group;
+      out[jw + lane] = val;
+      vmin = fminf(vmin, val);
+      vmax = fmaxf(vmax, val);
+    }
   }
+  // Value range of the chunk, one entry per wave (neutral where a wave wrote nothing): the
+  // selection scales its first radix digit to the range of the head's metric.
+#pragma unroll
+  for (int o = 16; o > 0; o >>= 1) {
+    vmin = fminf(vmin, __shfl_xor(vmin, o));
+    vmax = fmaxf(vmax, __shfl_xor(vmax, o));
+  }
+  if (lane == 0) range[((int64_t)hi * max_chunks + ch) * 4 + wave] = make_float2(vmin, vmax);
 }
 
 // ---- pooling + forced positions (stand-alone scores) -------------------------------------
@@ -471,6 +485,7 @@ static int launch_raw_t(const HostCfg& hc, const WsLayout& lay, const void* q, c
   const Geom& g = hc.g;
   float2* partial = reinterpret_cast<float2*>(ws + lay.partial);
   float* raw = reinterpret_cast<float*>(ws + lay.raw);
+  float2* range = reinterpret_cast<float2*>(ws + lay.range);
   const SeqTab tabA = tiles_for(hc.seq, g.chunk_keys, 0);
   const SeqTab tabB = tiles_for(hc.seq, g.chunk_keys, g.window);
   AllocIO io;
@@ -486,7 +501,7 @@ static int launch_raw_t(const HostCfg& hc, const WsLayout& lay, const void* q, c
   stage_mark(kStAccum, st);
   hipLaunchKernelGGL((score_accum_kernel<F32, D, NBM, RG>), gridB, dim3(256), 0, st, g, tabB, io,
                      n_alloc, bpp, (const char*)q, (const char*)k, (const float2*)partial, raw,
-                     lay.max_chunks, lay.rows_padded);
+                     range, lay.max_chunks, lay.rows_padded);
   return check_launch();
 }
 

@@ -2,18 +2,24 @@
 // with the fixed tie rule App. A.1 assumes (lowest position first), and the gather of the
 // retained rows into a dense per-head cache (Sec. 3.2, Eq. 3).
 //
-// Exact radix select on order-preserving 32-bit keys: an 11-bit top digit, then up to two
-// digits over the bits in which the surviving keys still differ.
-//   sel_hist - one workgroup (1024 threads) per slice of 1024 scores: [optionally the clipped
-//              max-pool + forced +inf of step 1,] an LDS histogram of the top digit, stored
-//              as the slice's own 16-bit counts (no shared hot counters).
-//   sel_tail - one workgroup per head: sums the slice histograms, fixes digit 0, re-scans the
-//              head's scores for digits 1 and 2, and counts, per block of 256 scores, the
-//              keys above and equal to the threshold T (no cross-workgroup counters or
-//              fences anywhere: kernel boundaries order the phases).
-//   sel_emit - one workgroup per block of 256 scores: prefix over earlier blocks, keep
-//              (key > T) plus the first r ties by position, write ascending positions and
-//              copy the K and V rows (16 bytes per lane, eight rows in flight per thread).
+// Exact radix select on order-preserving 32-bit keys.  The first digit is scaled to the range
+// of the head's metric: bin(key) = min((key - lo) >> shift, 2047), any non-decreasing map of
+// the key serves, so that the bin holding the k-th largest key holds few keys (the threshold
+// candidates) whatever the spread of the scores.
+//   sel_range - stand-alone scores only: (min, max) of the finite scores per slice (the fused
+//               path gets the range of the metric from the score kernel that produced it).
+//   sel_hist  - one workgroup (1024 threads) per slice of 1024 scores: [optionally the clipped
+//               max-pool + forced +inf of step 1,] an LDS histogram of the first digit, stored
+//               as the slice's own 16-bit suffix counts S[b] = #(keys of the slice in bins >= b)
+//               (no shared hot counters).
+//   sel_tail  - one workgroup per head: sums the suffix counts over the slices (which gives
+//               the bin T0 of the k-th key without a scan, and by one look-up per slice the
+//               rows above that bin), collects the candidates of bin T0, resolves the exact
+//               threshold key T among them with up to two further adaptive digits, and
+//               leaves, per slice, the kept rows and the ties before it.
+//   sel_emit  - one workgroup per slice: keep (key > T) plus the first r ties by position,
+//               write ascending positions and copy the K and V rows (16 bytes per lane).
+// No counter, flag or fence between workgroups anywhere: kernel boundaries order the phases.
 #include <string.h>
 
 #include "alloc_device.hpp"
@@ -21,40 +27,62 @@
 
 namespace lukv {
 
+constexpr int kCandLds = 4096;   // threshold candidates a head keeps in LDS (more: workspace)
+
 __device__ __forceinline__ unsigned key_of(float f) {
   unsigned u = __float_as_uint(f);
   if (u == 0x80000000u) u = 0u;  // -0 and +0 tie
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
-// Histogram increment that does not serialise when a whole wave hits one bin (pooled scores
-// come in runs of equal values, and a narrow score range puts every key in the same digit).
-__device__ __forceinline__ void hist_add(unsigned* lh, unsigned bin, bool act) {
+// first digit: non-decreasing in the key, clamped at both ends
+__device__ __forceinline__ unsigned bin_of(unsigned key, unsigned lo, unsigned shift) {
+  const unsigned d = key > lo ? (key - lo) >> shift : 0u;
+  return d < (unsigned)(kHistBins - 1) ? d : (unsigned)(kHistBins - 1);
+}
+
+// Histogram increment that returns the key's rank inside its bin (arrival order) and does not
+// serialise when a whole wave hits one bin (pooled scores come in runs of equal values).
+__device__ __forceinline__ unsigned hist_add(unsigned* lh, unsigned bin, bool act) {
   const unsigned long long m = __ballot(act);
-  if (m == 0ull) return;
+  if (m == 0ull) return 0u;
+  const int lane = threadIdx.x & 63;
   const int leader = __ffsll((long long)m) - 1;
   const unsigned first = (unsigned)__shfl((int)bin, leader);
   if (__ballot(act && bin != first) == 0ull) {
-    if ((int)(threadIdx.x & 63) == leader) atomicAdd(&lh[first], (unsigned)__popcll(m));
-  } else if (act) {
-    atomicAdd(&lh[bin], 1u);
+    unsigned at = 0;
+    if (lane == leader) at = atomicAdd(&lh[first], (unsigned)__popcll(m));
+    return (unsigned)__shfl((int)at, leader) + (unsigned)__popcll(m & ((1ull << lane) - 1ull));
   }
+  return act ? atomicAdd(&lh[bin], 1u) : 0u;
 }
 
 struct SelGeom {
-  int32_t n_layers, n_kv_heads, total_tokens, max_slices, max_blocks;
+  int32_t n_layers, n_kv_heads, total_tokens, max_slices;
   int32_t window, pool_kernel, n_sink;
+  int32_t range_chunk;    // positions covered by one group of range entries
+  int32_t range_per;      // entries per group
+  int32_t range_tail;     // trailing positions without entries (the window, fused path)
+  int32_t range_stride;   // entries per head in the range array
 };
 
-// Exclusive scan of one unsigned per thread over 1024 threads; part has 16 slots.
+// Inclusive scan over the 64 lanes of a wave with DPP row shifts and row broadcasts (no LDS
+// crossbar traffic): four shifts scan each row of 16 lanes, lane 15 of rows 0 and 2 is then
+// broadcast into rows 1 and 3, and lane 31 into rows 2 and 3.
+__device__ __forceinline__ unsigned wave_scan_incl(unsigned v) {
+  v += (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xf, 0xf, true);   // row_shr:1
+  v += (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xf, 0xf, true);   // row_shr:2
+  v += (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xf, 0xf, true);   // row_shr:4
+  v += (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xf, 0xf, true);   // row_shr:8
+  v += (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xa, 0xf, false);  // row_bcast:15
+  v += (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xc, 0xf, false);  // row_bcast:31
+  return v;
+}
+
+// Exclusive scan of one unsigned per thread over the workgroup (<= 16 waves); part has 16 slots.
 __device__ __forceinline__ unsigned scan1024(unsigned v, unsigned* part) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  unsigned incl = v;
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const unsigned up = __shfl_up(incl, o);
-    if (lane >= o) incl += up;
-  }
+  const unsigned incl = wave_scan_incl(v);
   __syncthreads();
   if (lane == 63) part[wave] = incl;
   __syncthreads();
@@ -63,15 +91,45 @@ __device__ __forceinline__ unsigned scan1024(unsigned v, unsigned* part) {
   return before;
 }
 
-// Slice histogram of the top digit (and, with POOL, the pooled scores themselves).
+// (min, max) of the finite scores of every slice, for scores that come from the caller.
+__global__ __launch_bounds__(1024) void sel_range_kernel(SelGeom sg, SeqTab tab, const float* scores,
+                                                         float2* range) {
+  __shared__ float mn_s[16], mx_s[16];
+  int seq, sl;
+  find_tile(tab, blockIdx.x, seq, sl);
+  const int kvh = blockIdx.y, layer = blockIdx.z, t = threadIdx.x;
+  const int tok0 = tab.cu[seq], L = tab.cu[seq + 1] - tok0;
+  const int hi = (seq * sg.n_layers + layer) * sg.n_kv_heads + kvh;
+  const float* src = scores + ((int64_t)layer * sg.n_kv_heads + kvh) * sg.total_tokens + tok0;
+  const int j = sl * kSliceElems + t;
+  const float s = j < L ? src[j] : INFINITY;
+  const bool fin = j < L && fabsf(s) < INFINITY;     // false for NaN too
+  float mn = fin ? s : INFINITY, mx = fin ? s : -INFINITY;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    mn = fminf(mn, __shfl_xor(mn, o));
+    mx = fmaxf(mx, __shfl_xor(mx, o));
+  }
+  if ((t & 63) == 0) { mn_s[t >> 6] = mn; mx_s[t >> 6] = mx; }
+  __syncthreads();
+  if (t == 0) {
+    for (int w = 1; w < 16; ++w) { mn = fminf(mn, mn_s[w]); mx = fmaxf(mx, mx_s[w]); }
+    range[(int64_t)hi * sg.range_stride + sl] = make_float2(mn, mx);
+  }
+}
+
+// Slice histogram of the first digit (and, with POOL, the pooled scores themselves).
 template <bool POOL>
 __global__ __launch_bounds__(1024) void sel_hist_kernel(SelGeom sg, SeqTab tab, AllocIO aio,
                                                         int n_alloc_blocks, const float* src_scores,
-                                                        float* pooled_out, unsigned* hist_parts,
-                                                        int32_t* status) {
+                                                        float* pooled_out, const float2* range,
+                                                        unsigned* hist_parts, uint2* head_dig,
+                                                        unsigned long long* by_bin, int32_t* status) {
   __shared__ __align__(16) char scratch[32768];
   unsigned* lh = reinterpret_cast<unsigned*>(scratch);                      // kHistBins counters
   float* rawt = reinterpret_cast<float*>(scratch + kHistBins * 4);           // slice + pool halo
+  unsigned* part = reinterpret_cast<unsigned*>(scratch + kHistBins * 4 + 4352);
+  unsigned* rng = part + 16;                                                 // min key, max key
   if ((int)blockIdx.x < n_alloc_blocks) {
     // extra workgroups of the fused path: budgets of one allocation problem each
     if (blockIdx.y == 0 && blockIdx.z == 0) alloc_phase_b(aio, blockIdx.x, scratch, (int)sizeof(scratch));
@@ -80,6 +138,7 @@ __global__ __launch_bounds__(1024) void sel_hist_kernel(SelGeom sg, SeqTab tab, 
   int seq, sl;
   find_tile(tab, blockIdx.x - n_alloc_blocks, seq, sl);
   const int kvh = blockIdx.y, layer = blockIdx.z, t = threadIdx.x;
+  const int lane = t & 63;
   const int tok0 = tab.cu[seq], L = tab.cu[seq + 1] - tok0;
   const int hi = (seq * sg.n_layers + layer) * sg.n_kv_heads + kvh;
   const int64_t base = ((int64_t)layer * sg.n_kv_heads + kvh) * sg.total_tokens + tok0;
@@ -91,232 +150,301 @@ __global__ __launch_bounds__(1024) void sel_hist_kernel(SelGeom sg, SeqTab tab, 
 
   lh[t] = 0;
   lh[t + 1024] = 0;
+  if (t < 2) rng[t] = t == 0 ? 0xFFFFFFFFu : 0u;
   const int j0 = sl * kSliceElems, j = j0 + t;
-  float s = 0.f;
+  const int P = L - sg.window, h = sg.pool_kernel >> 1;
+  float own = 0.f;
   if (POOL) {
-    // clipped max-pool over the prefix [0, P); window and sink positions are forced to +inf
-    const int P = L - sg.window, h = sg.pool_kernel >> 1;
     for (int i = t; i < kSliceElems + 2 * h; i += 1024) {
       const int jj = j0 - h + i;
       rawt[i] = (jj >= 0 && jj < P) ? src[jj] : -INFINITY;
     }
-    __syncthreads();
-    if (j < L) {
-      s = INFINITY;
-      if (j >= sg.n_sink && j < P) {
-        s = rawt[t];
-        for (int d = 1; d <= 2 * h; ++d) s = fmaxf(s, rawt[t + d]);
-      }
-      pooled[j] = s;
-    }
-  } else {
-    __syncthreads();
-    if (j < L) s = src[j];
+  } else if (j < L) {
+    own = src[j];
   }
-  hist_add(lh, key_of(s) >> 21, j < L);
+  // range of the head's metric: every workgroup of the head folds the same entries
+  float mn = INFINITY, mx = -INFINITY;
+  {
+    const int n_ent = (L - sg.range_tail + sg.range_chunk - 1) / sg.range_chunk * sg.range_per;
+    const float2* rp = range + (int64_t)hi * sg.range_stride;
+    if ((t & ~63) < n_ent) {
+      for (int e = t; e < n_ent; e += 1024) {
+        const float2 r = rp[e];
+        mn = fminf(mn, r.x);
+        mx = fmaxf(mx, r.y);
+      }
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) {
+        mn = fminf(mn, __shfl_xor(mn, o));
+        mx = fmaxf(mx, __shfl_xor(mx, o));
+      }
+    }
+  }
+  __syncthreads();   // counters cleared, halo staged
+  if (lane == 0 && mn <= mx) { atomicMin(&rng[0], key_of(mn)); atomicMax(&rng[1], key_of(mx)); }
   __syncthreads();
-  my_part[t] = (lh[2 * t] & 0xFFFFu) | (lh[2 * t + 1] << 16);   // counts <= 1024 fit 16 bits
+  unsigned lo = 0u, shift = 21u;   // without a usable range: the top 11 bits of the key
+  if (rng[0] <= rng[1]) {
+    const unsigned span = rng[1] - rng[0];
+    const int bits = span ? 32 - __clz(span) : 0;
+    lo = rng[0];
+    shift = bits > 11 ? (unsigned)(bits - 11) : 0u;
+  }
+  float s = own;
+  if (POOL && j < L) {
+    // clipped max-pool over the prefix [0, P); window and sink positions are forced to +inf
+    s = INFINITY;
+    if (j >= sg.n_sink && j < P) {
+      s = rawt[t];
+      for (int d = 1; d <= 2 * h; ++d) s = fmaxf(s, rawt[t + d]);
+    }
+    pooled[j] = s;
+  }
+  const unsigned key = key_of(s), bin = bin_of(key, lo, shift);
+  const unsigned rank = hist_add(lh, bin, j < L);
+  __syncthreads();
+  // suffix counts, descending bins: thread t owns bins 2047-2t and 2046-2t (packed word 1023-t)
+  const unsigned a1 = lh[2047 - 2 * t], a0 = lh[2046 - 2 * t];
+  const unsigned above = scan1024(a1 + a0, part);
+  const unsigned s_hi = above + a1, s_lo = s_hi + a0;          // <= 1024: fit 16 bits
+  my_part[1023 - t] = s_lo | (s_hi << 16);
+  // the slice's (key, position) pairs ordered by descending bin: the keys of bin b sit at
+  // [S[b+1], S[b]), so whoever knows the threshold bin reads its candidates directly
+  __syncthreads();
+  lh[2047 - 2 * t] = above;
+  lh[2046 - 2 * t] = s_hi;
+  __syncthreads();
+  if (j < L) by_bin[base + j0 + lh[bin] + rank] = ((unsigned long long)key << 32) | (unsigned)j;
+  if (t == 0 && sl == 0) head_dig[hi] = make_uint2(lo, shift);
+}
+
+// Exact threshold T among the n_c candidates of the list (the want-th largest, ties included)
+// by digits over the bits in which the candidates differ, and per-slice counts of candidates
+// above and at T.  Entries are (key << 32) | position.  All threads call it.
+template <class List>
+__device__ __forceinline__ void tail_resolve(List list, unsigned n_c, unsigned want, unsigned* lh,
+                                             unsigned* part, unsigned* sel, unsigned* s_gt,
+                                             unsigned* s_eq, unsigned& T_out, unsigned& r_eq_out) {
+  const int t = threadIdx.x, lane = t & 63;
+  // bits in which the candidates vary
+  {
+    unsigned cmin = 0xFFFFFFFFu, cmax = 0u;
+    for (unsigned i = t; i < n_c; i += 1024) {
+      const unsigned key = (unsigned)(list[i] >> 32);
+      cmin = key < cmin ? key : cmin;
+      cmax = key > cmax ? key : cmax;
+    }
+    if ((unsigned)(t & ~63) < n_c) {
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) {
+        const unsigned a2 = (unsigned)__shfl_xor((int)cmin, o), b2 = (unsigned)__shfl_xor((int)cmax, o);
+        cmin = a2 < cmin ? a2 : cmin;
+        cmax = b2 > cmax ? b2 : cmax;
+      }
+      if (lane == 0) { atomicMin(&sel[0], cmin); atomicMax(&sel[1], cmax); }
+    }
+  }
+  __syncthreads();
+  const unsigned cand_min = sel[0], vary = sel[0] ^ sel[1];
+  unsigned prefix = cand_min;        // all candidates equal: T is that key, `want` ties
+  if (vary != 0u) {
+    // digits of at most 11 bits from the top varying bit down; bits above it are common
+    int rest = 32 - __clz(vary);     // low bits still open
+    prefix = rest == 32 ? 0u : cand_min & ~((1u << rest) - 1u);
+    while (rest > 0) {
+      const int sh = rest > 11 ? rest - 11 : 0;
+      const unsigned mask = (1u << (rest - sh)) - 1u;
+      const unsigned hi_mask = rest == 32 ? 0u : ~((1u << rest) - 1u);
+      __syncthreads();
+      lh[t] = 0;
+      lh[t + 1024] = 0;
+      __syncthreads();
+      for (unsigned i = t; i < n_c; i += 1024) {
+        const unsigned key = (unsigned)(list[i] >> 32);
+        if ((key & hi_mask) == (prefix & hi_mask)) atomicAdd(&lh[(key >> sh) & mask], 1u);
+      }
+      __syncthreads();
+      const unsigned a1 = lh[2047 - 2 * t], a0 = lh[2046 - 2 * t];
+      const unsigned before = scan1024(a1 + a0, part);
+      if (before < want && want <= before + a1) { sel[2] = 2047 - 2 * t; sel[3] = want - before; }
+      else if (before + a1 < want && want <= before + a1 + a0) { sel[2] = 2046 - 2 * t; sel[3] = want - before - a1; }
+      __syncthreads();
+      prefix |= sel[2] << sh;
+      want = sel[3];
+      rest = sh;
+    }
+  }
+  const unsigned T = prefix;
+  for (unsigned i = t; i < n_c; i += 1024) {
+    const unsigned long long e = list[i];
+    const unsigned key = (unsigned)(e >> 32), sl = ((unsigned)e) >> 10;
+    if (key > T) atomicAdd(&s_gt[sl], 1u);
+    else if (key == T) atomicAdd(&s_eq[sl], 1u);
+  }
+  T_out = T;
+  r_eq_out = want;
+}
+
+// Candidates of bin T0: slice s holds them at by_bin[s*1024 + start[s] ..] (cnt[s] of them);
+// they are copied to list[off[s] ..], two slices per wave at a time.
+template <class List>
+__device__ __forceinline__ void tail_collect(List list, const unsigned long long* by_bin, int n_slices,
+                                             const unsigned* start, const unsigned* cnt,
+                                             const unsigned* off) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (int s0 = wave; s0 < n_slices; s0 += 16) {
+    const unsigned n = cnt[s0], at = off[s0];
+    const unsigned long long* src = by_bin + (int64_t)s0 * kSliceElems + start[s0];
+    for (unsigned c = lane; c < n; c += 64) list[at + c] = src[c];
+  }
 }
 
 // One workgroup per head: fixes the threshold key T and the number of ties to keep,
-// state[hi] = {T, ties at T to keep, budget after clamping, 0}, counts per block of 256
-// scores, and (if offsets_out is given) this head's row offset = sum of the budgets before it.
-// A thread owns the keys j = r*32768 + u*1024 + t (u < 32) of round r; with ONE (L <= 32768)
-// they are loaded once, all 32 loads in flight together, and stay in registers for every
-// phase; longer heads re-read them round by round.
-template <bool ONE>
-__global__ __launch_bounds__(1024) void sel_tail_kernel(SelGeom sg, SeqTab tab, const float* scores,
-                                                        const int32_t* budgets, const unsigned* hist_parts,
-                                                        uint4* state, uint2* block_cnt,
+// state[hi] = {T, ties at T to keep, budget after clamping, 0}; per slice the kept rows and
+// the ties in earlier slices; and (if offsets_out is given) this head's row offset = sum of
+// the budgets before it.
+__global__ __launch_bounds__(1024) void sel_tail_kernel(SelGeom sg, SeqTab tab, const int32_t* budgets,
+                                                        const unsigned* hist_parts,
+                                                        const unsigned long long* by_bin, uint4* state,
+                                                        uint2* slice_cnt, unsigned long long* cand_glob,
                                                         int64_t* offsets_out, int n_heads_total,
                                                         int32_t* status) {
-  constexpr int KPT = 32;
   __shared__ unsigned lh[kHistBins];
   __shared__ unsigned part[16];
-  __shared__ unsigned sel[2];
+  __shared__ unsigned sel[4];
+  __shared__ unsigned pick[3];
   __shared__ long long osum[16];
-  __shared__ unsigned short cg[16][KPT], ce[16][KPT];
+  __shared__ unsigned clo[1024], s_gt[1024], s_eq[1024], c_cnt[1024];
+  __shared__ unsigned long long cand_lds[kCandLds];
   const int hi = blockIdx.x, t = threadIdx.x;
   const int kvh = hi % sg.n_kv_heads, layer = (hi / sg.n_kv_heads) % sg.n_layers;
   const int seq = hi / (sg.n_kv_heads * sg.n_layers);
   const int tok0 = tab.cu[seq], L = tab.cu[seq + 1] - tok0;
-  const int n_slices = (L + kSliceElems - 1) / kSliceElems;
-  const int n_rounds = (L + 1024 * KPT - 1) / (1024 * KPT);
-  const float* keys_src = scores + ((int64_t)layer * sg.n_kv_heads + kvh) * sg.total_tokens + tok0;
+  const int n_slices = (L + kSliceElems - 1) / kSliceElems;     // <= 1024 (checked on the host)
+  const int64_t head_base = ((int64_t)layer * sg.n_kv_heads + kvh) * sg.total_tokens + tok0;
   const int lane = t & 63, wave = t >> 6;
+  uint2* my_cnt = slice_cnt + (int64_t)hi * sg.max_slices;
+  const unsigned* hp = hist_parts + (int64_t)hi * sg.max_slices * (kHistBins / 2) + (1023 - t);
 
-  unsigned key[KPT];   // order-preserving keys of this thread's scores (0 beyond L: below every real key's use)
-  auto load_round = [&](int r) {
-    float f[KPT];
+  // loads in flight together: suffix counts of the first 32 slices, budgets
+  unsigned w[32];
 #pragma unroll
-    for (int u = 0; u < KPT; ++u) {
-      const int jj = (r * KPT + u) * 1024 + t;
-      f[u] = jj < L ? keys_src[jj] : 0.f;
-    }
-#pragma unroll
-    for (int u = 0; u < KPT; ++u) key[u] = key_of(f[u]);
-  };
-  if (ONE) load_round(0);
-
-  if (offsets_out) {
-    long long acc = 0;
+  for (int u = 0; u < 32; ++u) w[u] = u < n_slices ? hp[(int64_t)u * (kHistBins / 2)] : 0u;
+  int kb = budgets[hi];
+  long long acc = 0;
+  if (offsets_out)
     for (int h2 = t; h2 < hi; h2 += 1024) acc += budgets[h2];
+
+  // suffix counts of the head: thread t owns packed word 1023-t, bins 2047-2t (high half) and
+  // 2046-2t; C[b] = keys of the head in bins >= b
+  unsigned c_hi = 0, c_lo = 0;
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-      const int lo = __shfl_xor((int)(acc & 0xFFFFFFFFll), o), hi32 = __shfl_xor((int)(acc >> 32), o);
-      acc += ((long long)hi32 << 32) | (unsigned)lo;
+  for (int u = 0; u < 32; ++u) { c_lo += w[u] & 0xFFFFu; c_hi += w[u] >> 16; }
+  for (int s0 = 32; s0 < n_slices; s0 += 32) {
+#pragma unroll
+    for (int u = 0; u < 32; ++u) w[u] = s0 + u < n_slices ? hp[(int64_t)(s0 + u) * (kHistBins / 2)] : 0u;
+#pragma unroll
+    for (int u = 0; u < 32; ++u) { c_lo += w[u] & 0xFFFFu; c_hi += w[u] >> 16; }
+  }
+  if (offsets_out) {
+    if (wave * 64 < hi) {
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) {
+        const int lo2 = __shfl_xor((int)(acc & 0xFFFFFFFFll), o), hi32 = __shfl_xor((int)(acc >> 32), o);
+        acc += ((long long)hi32 << 32) | (unsigned)lo2;
+      }
     }
     if (lane == 0) osum[wave] = acc;
-    __syncthreads();
-    if (t == 0) {
-      long long tot = 0;
-      for (int w = 0; w < 16; ++w) tot += osum[w];
-      offsets_out[hi] = tot;
-      if (hi == n_heads_total - 1) offsets_out[n_heads_total] = tot + budgets[hi];
-    }
   }
-
-  int kb = budgets[hi];
+  clo[t] = c_lo;
+  if (t < 2) sel[t] = t == 0 ? 0xFFFFFFFFu : 0u;   // min, max of the candidate keys
+  __syncthreads();
+  if (offsets_out && t == 0) {
+    long long tot = 0;
+    for (int w2 = 0; w2 < 16; ++w2) tot += osum[w2];
+    offsets_out[hi] = tot;
+    if (hi == n_heads_total - 1) offsets_out[n_heads_total] = tot + budgets[hi];
+  }
   if (kb < 0 || kb > L) {
     if (t == 0) atomicOr(status, LUKV_ST_CLAMPED);
     kb = kb < 0 ? 0 : L;
   }
-  if (kb == 0) {
-    // nothing kept: a threshold above every key and no ties
-    if (t == 0) state[hi] = make_uint4(0xFFFFFFFFu, 0u, 0u, 0u);
-    const unsigned n_blocks = (L + kEmitElems - 1) / kEmitElems;
-    for (unsigned b = t; b < n_blocks; b += 1024) block_cnt[(int64_t)hi * sg.max_blocks + b] = make_uint2(0u, 0u);
-    return;
-  }
-  // digit 0: thread t owns packed word 1023-t, i.e. bins 2047-2t (first) and 2046-2t
-  unsigned c_hi = 0, c_lo = 0;
+  // a head that keeps nothing runs the same code with k = 1 and overrides the result
+  const bool keep_none = kb == 0;
+  if (keep_none) kb = 1;
+  // T0 = the largest bin with C[T0] >= kb; C is non-increasing in the bin, so exactly one
+  // thread sees the step.  `want` keys are still needed from bin T0.
   {
-    const unsigned* hp = hist_parts + (int64_t)hi * sg.max_slices * (kHistBins / 2) + (1023 - t);
-    for (int s0 = 0; s0 < n_slices; s0 += 32) {
-      unsigned w[32];   // independent loads first: one memory latency per 32 slices
-#pragma unroll
-      for (int u = 0; u < 32; ++u) w[u] = s0 + u < n_slices ? hp[(int64_t)(s0 + u) * (kHistBins / 2)] : 0u;
-#pragma unroll
-      for (int u = 0; u < 32; ++u) { c_lo += w[u] & 0xFFFFu; c_hi += w[u] >> 16; }
-    }
-  }
-  unsigned want = (unsigned)kb, prefix = 0;
-  {
-    const unsigned before = scan1024(c_hi + c_lo, part);
-    if (before < want && want <= before + c_hi) { sel[0] = 2047 - 2 * t; sel[1] = want - before; }
-    else if (before + c_hi < want && want <= before + c_hi + c_lo) { sel[0] = 2046 - 2 * t; sel[1] = want - before - c_hi; }
-    __syncthreads();
-    prefix = sel[0] << 21;
-    want = sel[1];
-  }
-  // The keys that share digit 0 usually differ only in some low bits: find the bits in which
-  // they vary at all and spread those over the remaining digits (at most 11 + 10 bits), so
-  // that a narrow range of scores still fills the histogram evenly.
-  if (t < 2) sel[t] = t == 0 ? 0xFFFFFFFFu : 0u;   // min, max of the candidate keys
-  __syncthreads();
-  {
-    unsigned cmin = 0xFFFFFFFFu, cmax = 0u;
-    for (int r = 0; r < n_rounds; ++r) {
-      if (!ONE) load_round(r);
-#pragma unroll
-      for (int u = 0; u < KPT; ++u)
-        if ((r * KPT + u) * 1024 + t < L && (key[u] >> 21) == (prefix >> 21)) {
-          cmin = key[u] < cmin ? key[u] : cmin;
-          cmax = key[u] > cmax ? key[u] : cmax;
-        }
-    }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-      const unsigned a2 = (unsigned)__shfl_xor((int)cmin, o), b2 = (unsigned)__shfl_xor((int)cmax, o);
-      cmin = a2 < cmin ? a2 : cmin;
-      cmax = b2 > cmax ? b2 : cmax;
-    }
-    if (lane == 0) { atomicMin(&sel[0], cmin); atomicMax(&sel[1], cmax); }
+    const unsigned above = t ? clo[t - 1] : 0u;    // C[2048 - 2t]
+    const unsigned k = (unsigned)kb;
+    if (c_hi >= k && above < k) { pick[0] = 2047 - 2 * t; pick[1] = k - above; pick[2] = c_hi - above; }
+    else if (c_lo >= k && c_hi < k) { pick[0] = 2046 - 2 * t; pick[1] = k - c_hi; pick[2] = c_lo - c_hi; }
   }
   __syncthreads();
-  const unsigned cand_min = sel[0], vary = sel[0] ^ sel[1];
-  __syncthreads();
-  if (vary == 0u) {
-    prefix = cand_min;             // every candidate is the same key: T is that key, `want` ties
+  const unsigned T0 = pick[0], want0 = pick[1], n_cand = pick[2];
+  // per slice, from its suffix counts: rows above bin T0, and where its candidates sit
+  unsigned n_s = 0;
+  if (t < n_slices) {
+    const unsigned* sp = hist_parts + ((int64_t)hi * sg.max_slices + t) * (kHistBins / 2);
+    const unsigned w0 = sp[T0 >> 1];
+    unsigned up, dn;   // S[T0 + 1], S[T0]
+    if (T0 & 1u) {
+      dn = w0 >> 16;
+      up = T0 == (unsigned)(kHistBins - 1) ? 0u : (sp[(T0 >> 1) + 1] & 0xFFFFu);
+    } else {
+      dn = w0 & 0xFFFFu;
+      up = w0 >> 16;
+    }
+    n_s = dn - up;
+    s_gt[t] = up;
+    s_eq[t] = 0u;
+    c_cnt[t] = n_s;
+  }
+  unsigned* c_off = clo;   // free after the pick above
+  if (n_slices <= 64) {
+    if (wave == 0) c_off[lane] = wave_scan_incl(n_s) - n_s;
   } else {
-    const int vb = 31 - __clz(vary);                    // top varying bit (<= 20)
-    const int shift1 = vb > 10 ? vb - 10 : 0;           // digit 1: bits vb .. shift1
-    const unsigned mask1 = (2u << (vb - shift1)) - 1u;
-    prefix = cand_min & ~((2u << vb) - 1u);             // bits above vb are common
-    lh[t] = 0;
-    lh[t + 1024] = 0;
-    __syncthreads();
-    for (int r = 0; r < n_rounds; ++r) {
-      if (!ONE) load_round(r);
-#pragma unroll
-      for (int u = 0; u < KPT; ++u)
-        if ((r * KPT + u) * 1024 + t < L && (key[u] >> (vb + 1)) == (prefix >> (vb + 1)))
-          atomicAdd(&lh[(key[u] >> shift1) & mask1], 1u);
-    }
-    __syncthreads();
-    {
-      const unsigned a1 = lh[2047 - 2 * t], a0 = lh[2046 - 2 * t];
-      const unsigned before = scan1024(a1 + a0, part);
-      if (before < want && want <= before + a1) { sel[0] = 2047 - 2 * t; sel[1] = want - before; }
-      else if (before + a1 < want && want <= before + a1 + a0) { sel[0] = 2046 - 2 * t; sel[1] = want - before - a1; }
-      __syncthreads();
-      prefix |= sel[0] << shift1;
-      want = sel[1];
-    }
-    if (shift1 > 0) {
-      // digit 2: the remaining low bits (at most 10)
-      __syncthreads();
-      lh[t] = 0;
-      __syncthreads();
-      const unsigned mask2 = (1u << shift1) - 1u;
-      for (int r = 0; r < n_rounds; ++r) {
-        if (!ONE) load_round(r);
-#pragma unroll
-        for (int u = 0; u < KPT; ++u)
-          if ((r * KPT + u) * 1024 + t < L && (key[u] >> shift1) == (prefix >> shift1))
-            atomicAdd(&lh[key[u] & mask2], 1u);
-      }
-      __syncthreads();
-      {
-        const unsigned a = lh[1023 - t];
-        const unsigned before = scan1024(a, part);
-        if (before < want && want <= before + a) { sel[0] = 1023 - t; sel[1] = want - before; }
-        __syncthreads();
-        prefix |= sel[0];
-        want = sel[1];
-      }
-    }
+    const unsigned o = scan1024(n_s, part);
+    c_off[t] = o;
   }
-  const unsigned T = prefix;
-  if (t == 0) state[hi] = make_uint4(T, want, (unsigned)kb, 0u);
-  // per block of 256 scores: keys above T and keys equal to T.  Key (r, u, t) sits in block
-  // (r*KPT + u)*4 + t/256: four waves share a block, ballots count, LDS joins the four.
-  for (int r = 0; r < n_rounds; ++r) {
-    if (!ONE) load_round(r);
+  __syncthreads();
+  unsigned T, r_eq;
+  if (n_cand <= (unsigned)kCandLds) {
+    tail_collect(cand_lds, by_bin + head_base, n_slices, s_gt, c_cnt, c_off);
     __syncthreads();
-#pragma unroll
-    for (int u = 0; u < KPT; ++u) {
-      const bool in = (r * KPT + u) * 1024 + t < L;
-      const unsigned long long mg = __ballot(in && key[u] > T), me = __ballot(in && key[u] == T);
-      if (lane == 0) { cg[wave][u] = (unsigned short)__popcll(mg); ce[wave][u] = (unsigned short)__popcll(me); }
-    }
+    tail_resolve(cand_lds, n_cand, want0, lh, part, sel, s_gt, s_eq, T, r_eq);
+  } else {
+    unsigned long long* list = cand_glob + head_base;
+    tail_collect(list, by_bin + head_base, n_slices, s_gt, c_cnt, c_off);
     __syncthreads();
-    if (t < 4 * KPT) {
-      const int u = t >> 2, q = t & 3;
-      const int b = (r * KPT + u) * 4 + q;
-      if (b * kEmitElems < L) {
-        unsigned gt = 0, eq = 0;
-#pragma unroll
-        for (int w = 0; w < 4; ++w) { gt += cg[4 * q + w][u]; eq += ce[4 * q + w][u]; }
-        block_cnt[(int64_t)hi * sg.max_blocks + b] = make_uint2(gt, eq);
-      }
+    tail_resolve(list, n_cand, want0, lh, part, sel, s_gt, s_eq, T, r_eq);
+  }
+  __syncthreads();
+  // nothing kept: a threshold above every key and no ties
+  if (t == 0) state[hi] = keep_none ? make_uint4(0xFFFFFFFFu, 0u, 0u, 0u) : make_uint4(T, r_eq, (unsigned)kb, 0u);
+  if (n_slices <= 64) {
+    if (wave == 0) {
+      const unsigned g = lane < n_slices && !keep_none ? s_gt[lane] : 0u;
+      const unsigned e = lane < n_slices && !keep_none ? s_eq[lane] : 0u;
+      const unsigned g_before = wave_scan_incl(g) - g, e_before = wave_scan_incl(e) - e;
+      if (lane < n_slices) my_cnt[lane] = make_uint2(g_before, e_before);
     }
+  } else {
+    const unsigned g = t < n_slices && !keep_none ? s_gt[t] : 0u;
+    const unsigned e = t < n_slices && !keep_none ? s_eq[t] : 0u;
+    const unsigned g_before = scan1024(g, part);
+    const unsigned e_before = scan1024(e, part);
+    if (t < n_slices) my_cnt[t] = make_uint2(g_before, e_before);
   }
 }
 
+constexpr int kEmitElems = 256;    // scores one workgroup of the emit/gather kernel owns
+
+// One workgroup per block of 256 scores, four blocks to a slice.  The rows kept before the
+// slice come from sel_tail; the (up to three) earlier blocks of the slice are re-judged here.
 template <int ROW_BYTES>
 __global__ __launch_bounds__(256) void sel_emit_kernel(SelGeom sg, SeqTab tab, const float* scores,
-                                                       const uint4* state, const uint2* block_cnt,
+                                                       const uint4* state, const uint2* slice_cnt,
                                                        const int64_t* offsets, const char* k,
                                                        const char* v, int64_t sl_bytes,
                                                        int64_t sh_bytes, int64_t st_bytes,
@@ -331,33 +459,34 @@ __global__ __launch_bounds__(256) void sel_emit_kernel(SelGeom sg, SeqTab tab, c
   const int tok0 = tab.cu[seq], L = tab.cu[seq + 1] - tok0;
   const int hi = (seq * sg.n_layers + layer) * sg.n_kv_heads + kvh;
   const float* src = scores + ((int64_t)layer * sg.n_kv_heads + kvh) * sg.total_tokens + tok0;
-  const uint4 stt = state[hi];
-  const unsigned T = stt.x, r_eq = stt.y;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-
+  const int sl = blk >> 2, q = blk & 3;
   const int j = blk * kEmitElems + threadIdx.x;
   const bool in = j < L;
-  const unsigned key = in ? key_of(src[j]) : 0u;
-
-  // kept rows in earlier blocks of this head
-  unsigned gb = 0, eb = 0;
-  for (int s2 = threadIdx.x; s2 < blk; s2 += 256) {
-    const uint2 c = block_cnt[(int64_t)hi * sg.max_blocks + s2];
-    gb += c.x;
-    eb += c.y;
-  }
+  // scores of this block and of the earlier blocks of the slice (those are full blocks)
+  float fq[3];
 #pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    gb += __shfl_xor(gb, o);
-    eb += __shfl_xor(eb, o);
+  for (int p = 0; p < 3; ++p) fq[p] = p < q ? src[sl * kSliceElems + p * kEmitElems + (int)threadIdx.x] : 0.f;
+  const unsigned key = in ? key_of(src[j]) : 0u;
+  const uint4 stt = state[hi];
+  const uint2 before = slice_cnt[(int64_t)hi * sg.max_slices + sl];
+  const int64_t head_row0 = offsets[hi];
+  const unsigned T = stt.x, r_eq = stt.y;
+
+  unsigned pg = 0, pe = 0;
+#pragma unroll
+  for (int p = 0; p < 3; ++p) {
+    const unsigned kp = key_of(fq[p]);
+    pg += (unsigned)__popcll(__ballot(p < q && kp > T));
+    pe += (unsigned)__popcll(__ballot(p < q && kp == T));
   }
   const bool is_eq = in && key == T;
   const unsigned long long em = __ballot(is_eq);
-  if (lane == 0) { red_g[wave] = gb; red_e[wave] = eb; weq[wave] = (unsigned)__popcll(em); }
+  if (lane == 0) { red_g[wave] = pg; red_e[wave] = pe; weq[wave] = (unsigned)__popcll(em); }
   __syncthreads();
-  const unsigned gt_before = red_g[0] + red_g[1] + red_g[2] + red_g[3];
-  const unsigned eq_before = red_e[0] + red_e[1] + red_e[2] + red_e[3];
-  const int64_t row0 = offsets[hi] + gt_before + (eq_before < r_eq ? eq_before : r_eq);
+  const unsigned gt_before = before.x + red_g[0] + red_g[1] + red_g[2] + red_g[3];
+  const unsigned eq_before = before.y + red_e[0] + red_e[1] + red_e[2] + red_e[3];
+  const int64_t row0 = head_row0 + gt_before + (eq_before < r_eq ? eq_before : r_eq);
 
   // rank of this tie among the ties of the head, in position order
   const unsigned long long lt_mask = (1ull << lane) - 1ull;
@@ -412,11 +541,11 @@ __global__ __launch_bounds__(256) void sel_emit_kernel(SelGeom sg, SeqTab tab, c
 
 template <int ROW_BYTES>
 static void launch_emit(dim3 grid, hipStream_t st, SelGeom sg, const SeqTab& tab, const float* pooled,
-                        const uint4* state, const uint2* block_cnt, const int64_t* offsets,
+                        const uint4* state, const uint2* slice_cnt, const int64_t* offsets,
                         const void* k, const void* v, const Geom& g, int esize, int32_t* kept_idx,
                         void* k_out, void* v_out, int64_t out_rows, int32_t* status) {
   hipLaunchKernelGGL((sel_emit_kernel<ROW_BYTES>), grid, dim3(256), 0, st, sg, tab, pooled, state,
-                     block_cnt, offsets, (const char*)k, (const char*)v, g.sl * esize, g.sh * esize,
+                     slice_cnt, offsets, (const char*)k, (const char*)v, g.sl * esize, g.sh * esize,
                      g.st * esize, kept_idx, (char*)k_out, (char*)v_out, out_rows, status);
 }
 
@@ -430,43 +559,48 @@ int launch_select_compact(const HostCfg& hc, const WsLayout& lay, const AllocIO*
   const Geom& g = hc.g;
   const SeqTab tabH = tiles_for(hc.seq, kSliceElems, 0);
   const SeqTab tabE = tiles_for(hc.seq, kEmitElems, 0);
-  SelGeom sg{g.n_layers, g.n_kv_heads, g.total_tokens, lay.max_slices, lay.max_blocks,
-             g.window, g.pool_kernel, g.n_sink};
+  SelGeom sg{g.n_layers, g.n_kv_heads, g.total_tokens, lay.max_slices,
+             g.window, g.pool_kernel, g.n_sink,
+             pool ? g.chunk_keys : kSliceElems, pool ? 4 : 1, pool ? g.window : 0,
+             pool ? lay.max_chunks * 4 : lay.max_slices};
   unsigned* hist = reinterpret_cast<unsigned*>(ws + lay.hist);
+  float2* range = reinterpret_cast<float2*>(ws + lay.range);
+  uint2* head_dig = reinterpret_cast<uint2*>(ws + lay.head_dig);
   uint4* state = reinterpret_cast<uint4*>(ws + lay.sel_state);
-  uint2* block_cnt = reinterpret_cast<uint2*>(ws + lay.slice_cnt);
+  uint2* slice_cnt = reinterpret_cast<uint2*>(ws + lay.slice_cnt);
+  unsigned long long* by_bin = reinterpret_cast<unsigned long long*>(ws + lay.by_bin);
+  unsigned long long* cand = reinterpret_cast<unsigned long long*>(ws + lay.cand);
   AllocIO io;
   memset(&io, 0, sizeof(io));
   int n_alloc = 0;
   if (aio) { io = *aio; n_alloc = aio->n_problems; }
-  dim3 gridH(tabH.tile0[tabH.n_seqs] + n_alloc, g.n_kv_heads, g.n_layers);
+  const int n_tiles = tabH.tile0[tabH.n_seqs];
+  dim3 gridH(n_tiles + n_alloc, g.n_kv_heads, g.n_layers);
+  dim3 gridR(n_tiles, g.n_kv_heads, g.n_layers);
   dim3 gridE(tabE.tile0[tabE.n_seqs], g.n_kv_heads, g.n_layers);
   stage_mark(kStHist, st);
-  if (pool)
+  if (pool) {
     hipLaunchKernelGGL(sel_hist_kernel<true>, gridH, dim3(1024), 0, st, sg, tabH, io, n_alloc, scores_in,
-                       pooled_out, hist, status);
-  else
+                       pooled_out, (const float2*)range, hist, head_dig, by_bin, status);
+  } else {
+    hipLaunchKernelGGL(sel_range_kernel, gridR, dim3(1024), 0, st, sg, tabH, scores_in, range);
     hipLaunchKernelGGL(sel_hist_kernel<false>, gridH, dim3(1024), 0, st, sg, tabH, io, n_alloc, scores_in,
-                       (float*)nullptr, hist, status);
+                       (float*)nullptr, (const float2*)range, hist, head_dig, by_bin, status);
+  }
   const float* sel_scores = pool ? pooled_out : scores_in;
   stage_mark(kStTail, st);
-  if (hc.max_len <= 32768)
-    hipLaunchKernelGGL(sel_tail_kernel<true>, dim3(hc.n_hi), dim3(1024), 0, st, sg, tabH, sel_scores, budgets,
-                       (const unsigned*)hist, state, block_cnt, make_offsets ? offsets : (int64_t*)nullptr,
-                       hc.n_hi, status);
-  else
-    hipLaunchKernelGGL(sel_tail_kernel<false>, dim3(hc.n_hi), dim3(1024), 0, st, sg, tabH, sel_scores, budgets,
-                       (const unsigned*)hist, state, block_cnt, make_offsets ? offsets : (int64_t*)nullptr,
-                       hc.n_hi, status);
+  hipLaunchKernelGGL(sel_tail_kernel, dim3(hc.n_hi), dim3(1024), 0, st, sg, tabH, budgets,
+                     (const unsigned*)hist, (const unsigned long long*)by_bin, state, slice_cnt, cand,
+                     make_offsets ? offsets : (int64_t*)nullptr, hc.n_hi, status);
   stage_mark(kStEmit, st);
   const int esize = g.f32 ? 4 : 2;
   const int row_bytes = g.head_dim * esize;
   if (row_bytes == 128)
-    launch_emit<128>(gridE, st, sg, tabE, sel_scores, state, block_cnt, offsets, k, v, g, esize, kept_idx, k_out, v_out, out_rows, status);
+    launch_emit<128>(gridE, st, sg, tabE, sel_scores, state, slice_cnt, offsets, k, v, g, esize, kept_idx, k_out, v_out, out_rows, status);
   else if (row_bytes == 256)
-    launch_emit<256>(gridE, st, sg, tabE, sel_scores, state, block_cnt, offsets, k, v, g, esize, kept_idx, k_out, v_out, out_rows, status);
+    launch_emit<256>(gridE, st, sg, tabE, sel_scores, state, slice_cnt, offsets, k, v, g, esize, kept_idx, k_out, v_out, out_rows, status);
   else if (row_bytes == 512)
-    launch_emit<512>(gridE, st, sg, tabE, sel_scores, state, block_cnt, offsets, k, v, g, esize, kept_idx, k_out, v_out, out_rows, status);
+    launch_emit<512>(gridE, st, sg, tabE, sel_scores, state, slice_cnt, offsets, k, v, g, esize, kept_idx, k_out, v_out, out_rows, status);
   else
     return LUKV_EDTYPE;
   return check_launch();

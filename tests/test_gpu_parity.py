@@ -8,6 +8,7 @@ tighter than the 1e-3 score tolerance), and the compacted rows must be bitwise t
 the GPU's indices name.
 """
 import dataclasses
+import zlib
 
 import numpy as np
 import pytest
@@ -255,6 +256,71 @@ def test_select_budget_extremes_and_clamp():
     kept = out["kept_idx"].cpu().numpy()
     assert np.array_equal(kept[:L], np.arange(L))
     assert np.array_equal(kept[L:L + 2], O.select(pooled[1, 0], 2))
+
+
+def _adversarial_scores(kind, rng, shape):
+    """Score distributions that stress the radix select: candidates by the thousand, a digit
+    that does not discriminate, clamped end bins, both signs, infinities, zeros of both signs."""
+    n = int(np.prod(shape))
+    if kind == "all_equal":
+        x = np.full(n, 0.375, np.float32)
+    elif kind == "two_values":
+        x = rng.integers(0, 2, n).astype(np.float32)
+    elif kind == "quantised":
+        x = (rng.integers(0, 37, n) / 4).astype(np.float32)
+    elif kind == "narrow_band":
+        x = (1.0 + rng.integers(0, 3000, n) * 2.0 ** -23).astype(np.float32)      # few thousand ulps wide
+    elif kind == "wide_signed":
+        x = (rng.standard_normal(n) * 10.0 ** rng.uniform(-30, 30, n)).astype(np.float32)
+        x[rng.integers(0, n, n // 50)] = 0.0
+        x[rng.integers(0, n, n // 50)] = -0.0
+        x[rng.integers(0, n, n // 100)] = np.inf
+        x[rng.integers(0, n, n // 100)] = -np.inf
+    elif kind == "denormal_and_zero":
+        x = (rng.integers(-40, 40, n) * np.float32(1e-45)).astype(np.float32)
+    elif kind == "mostly_zero_few_heavy":
+        x = np.zeros(n, np.float32)
+        hot = rng.integers(0, n, n // 200)
+        x[hot] = rng.random(hot.size).astype(np.float32)
+    elif kind == "lognormal":
+        x = np.exp(3.0 * rng.standard_normal(n)).astype(np.float32)
+    else:
+        raise KeyError(kind)
+    return x.reshape(shape)
+
+
+@pytest.mark.parametrize("kind", ["all_equal", "two_values", "quantised", "narrow_band", "wide_signed",
+                                  "denormal_and_zero", "mostly_zero_few_heavy", "lognormal"])
+def test_select_adversarial_score_distributions(kind):
+    print("case", kind, flush=True)
+    wl = synth.Workload(name="sel_" + kind, n_layers=1, n_q_heads=4, n_kv_heads=4, head_dim=64,
+                        seq_lens=[20011, 5000], window=16, pool_kernel=7, n_sink=4, dtype=synth.BF16,
+                        keep_ratio=0.2, n_grid=8, heavy_frac=0.0, seed=99, q_gain=64.0)
+    p = Problem(wl)
+    rng = np.random.default_rng(zlib.crc32(kind.encode()))
+    pooled = _adversarial_scores(kind, rng, (1, wl.n_kv_heads, wl.total_len))
+    cu = wl.cu_seqlens
+    budgets = []
+    for s in range(wl.n_seqs):
+        L = int(cu[s + 1] - cu[s])
+        budgets += [L // 3, 1, L - 1, int(rng.integers(1, L))]
+    budgets = np.array(budgets, np.int32)
+    offsets = O.offsets_of(budgets)
+    out = p.new_outputs(rows=int(offsets[-1]))
+    lukv.lukv_select_compact(p.cfg, dev(pooled), dev(budgets), dev(offsets), p.k, p.v,
+                             out["kept_idx"].numel(), out["kept_idx"], out["k_out"], out["v_out"],
+                             out["status"][:1], p.ws)
+    torch.cuda.synchronize()
+    assert int(out["status"][0]) == 0
+    kept, ko, vo = out["kept_idx"].cpu().numpy(), host_bits(out["k_out"]), host_bits(out["v_out"])
+    for s in range(wl.n_seqs):
+        for c in range(wl.n_kv_heads):
+            hi = s * wl.n_kv_heads + c
+            a, b = int(offsets[hi]), int(offsets[hi + 1])
+            want = O.select(pooled[0, c, cu[s]:cu[s + 1]], int(budgets[hi]))
+            assert np.array_equal(kept[a:b], want), (kind, s, c)
+            assert np.array_equal(ko[a:b], p.data["k"][0, c, cu[s]:cu[s + 1]][want])
+            assert np.array_equal(vo[a:b], p.data["v"][0, c, cu[s]:cu[s + 1]][want])
 
 
 def test_host_side_refusals_enqueue_nothing():
