@@ -135,7 +135,8 @@ __device__ inline void alloc_phase_a(const AllocIO& io, int p, int blk) {
 }
 
 // Phase B for problem p (after phase A's flags are visible).  Any workgroup size that is a
-// multiple of 64 from 256 to 1024; lds: scratch of lds_bytes (>= 32 KiB), free for this call.
+// multiple of 64 from 256 to 1024; lds: scratch of lds_bytes (>= 32 KiB; with 48 KiB and 1024
+// threads a small problem takes the fast selection), free for this call.
 // Everything a thread walks more than once (vertex flags, knots, curves, segments, per-head
 // sums) is staged in LDS when the problem fits (up to 1024 segments and 1024 heads; larger
 // problems use the workspace and global memory, slower but the same arithmetic).  The radix
@@ -177,6 +178,7 @@ __device__ inline void alloc_phase_b(const AllocIO& io, int p, char* lds, int ld
     sel[0] = 0ull; sel[1] = 0ull; sel[2] = ~0ull; sel[3] = 0ull;
   }
   if (small) {
+    // every global load of the staging is issued before the first barrier
     for (int i = t; i < NH * words; i += nt) l_mask[i] = 0ull;
     for (int h = t; h < NH; h += nt) {
       l_lb[h] = io.b_min[hbase + h];
@@ -185,11 +187,24 @@ __device__ inline void alloc_phase_b(const AllocIO& io, int p, char* lds, int ld
       h_gt[h] = 0;
       h_eq[h] = 0;
     }
-    __syncthreads();
-    for (int i = t; i < (int)nseg; i += nt) {
-      l_kn[i] = kn[i];
-      l_cu[i] = cu[i];
-      if (vtx[i]) { const int h = i / Gp, g = i - h * Gp; atomicOr(&l_mask[h * words + (g >> 6)], 1ull << (g & 63)); }
+    if (nseg <= nt) {
+      const bool in = t < (int)nseg;
+      const int32_t vk = in ? kn[t] : 0;
+      const float vc = in ? cu[t] : 0.f;
+      const int32_t vv = in ? vtx[t] : 0;
+      __syncthreads();
+      if (in) {
+        l_kn[t] = vk;
+        l_cu[t] = vc;
+        if (vv) { const int h = t / Gp, g = t - h * Gp; atomicOr(&l_mask[h * words + (g >> 6)], 1ull << (g & 63)); }
+      }
+    } else {
+      __syncthreads();
+      for (int i = t; i < (int)nseg; i += nt) {
+        l_kn[i] = kn[i];
+        l_cu[i] = cu[i];
+        if (vtx[i]) { const int h = i / Gp, g = i - h * Gp; atomicOr(&l_mask[h * words + (g >> 6)], 1ull << (g & 63)); }
+      }
     }
   }
   __syncthreads();
@@ -235,21 +250,98 @@ __device__ inline void alloc_phase_b(const AllocIO& io, int p, char* lds, int ld
     sum_w += w;
     if (w) { k_and &= key; k_or |= key; }
   }
-  // workgroup sums: most threads hold nothing, so only the others touch the LDS counters
-  if (sum_min) atomicAdd(reinterpret_cast<unsigned long long*>(&red[0]), (unsigned long long)sum_min);
-  if (sum_w) {
-    atomicAdd(reinterpret_cast<unsigned long long*>(&red[1]), (unsigned long long)sum_w);
-    atomicAnd(&sel[2], k_and);
-    atomicOr(&sel[3], k_or);
+  // workgroup sums: every wave reduces its lanes with DPP steps (64-bit values as two halves:
+  // sums of 16-bit pieces of values below 2^32 cannot overflow a lane), then one LDS atomic
+  // per wave and quantity
+  {
+    auto add = [](unsigned a, unsigned b) { return a + b; };
+    auto band = [](unsigned a, unsigned b) { return a & b; };
+    auto bor = [](unsigned a, unsigned b) { return a | b; };
+    const bool small_vals = (unsigned long long)sum_min < (1ull << 32) && (unsigned long long)sum_w < (1ull << 32);
+    if (__ballot(!small_vals) == 0ull) {
+      const unsigned m_lo = wave_reduce_to_last((unsigned)sum_min & 0xFFFFu, 0u, add);
+      const unsigned m_hi = wave_reduce_to_last((unsigned)sum_min >> 16, 0u, add);
+      const unsigned w_lo = wave_reduce_to_last((unsigned)sum_w & 0xFFFFu, 0u, add);
+      const unsigned w_hi = wave_reduce_to_last((unsigned)sum_w >> 16, 0u, add);
+      const unsigned a_lo = wave_reduce_to_last((unsigned)k_and, ~0u, band);
+      const unsigned a_hi = wave_reduce_to_last((unsigned)(k_and >> 32), ~0u, band);
+      const unsigned o_lo = wave_reduce_to_last((unsigned)k_or, 0u, bor);
+      const unsigned o_hi = wave_reduce_to_last((unsigned)(k_or >> 32), 0u, bor);
+      const unsigned any_bad = wave_reduce_to_last((unsigned)bad, 0u, bor);
+      if (lane == 63) {
+        const unsigned long long wm = ((unsigned long long)m_hi << 16) + m_lo;
+        const unsigned long long ww = ((unsigned long long)w_hi << 16) + w_lo;
+        if (wm) atomicAdd(reinterpret_cast<unsigned long long*>(&red[0]), wm);
+        if (ww) {
+          atomicAdd(reinterpret_cast<unsigned long long*>(&red[1]), ww);
+          atomicAnd(&sel[2], ((unsigned long long)a_hi << 32) | a_lo);
+          atomicOr(&sel[3], ((unsigned long long)o_hi << 32) | o_lo);
+        }
+        if (any_bad) atomicAdd(reinterpret_cast<unsigned long long*>(&red[2]), 1ull);
+      }
+    } else {
+      if (sum_min) atomicAdd(reinterpret_cast<unsigned long long*>(&red[0]), (unsigned long long)sum_min);
+      if (sum_w) {
+        atomicAdd(reinterpret_cast<unsigned long long*>(&red[1]), (unsigned long long)sum_w);
+        atomicAnd(&sel[2], k_and);
+        atomicOr(&sel[3], k_or);
+      }
+      if (bad) atomicAdd(reinterpret_cast<unsigned long long*>(&red[2]), 1ull);
+    }
   }
-  if (bad) atomicAdd(reinterpret_cast<unsigned long long*>(&red[2]), 1ull);
   __syncthreads();
   const long long R = io.B[p] - red[0];
   const bool infeasible = red[2] != 0 || R < 0 || R > red[1];
   const bool active = !infeasible && R > 0;
 
-  // weighted radix select of the threshold gain g*: W(> g*) < R <= W(>= g*), on wave 0
-  if (active && wave == 0) {
+  // weighted radix select of the threshold gain g*: W(> g*) < R <= W(>= g*)
+  // fast form: one segment per thread, 32-bit unit counts, digits of up to 11 bits over the
+  // bits in which the live keys differ, from the top varying bit down; stops as soon as the
+  // chosen bin holds a single segment
+  const bool fast = small && nt == 1024 && lds_bytes >= 49152 && red[1] < (1ll << 31);
+  if (active && fast) {
+    unsigned* bh = reinterpret_cast<unsigned*>(lds + 32768);   // kHistBins unit counts
+    unsigned* bc = bh + kHistBins;                             // kHistBins segment counts
+    unsigned* spart = reinterpret_cast<unsigned*>(sm);         // 16 slots for the scans
+    unsigned* pick32 = reinterpret_cast<unsigned*>(lds + 152); // bin, units still wanted
+    const unsigned long long differ = sel[2] ^ sel[3];
+    const unsigned long long mykey = t < nseg ? skey[t] : 0ull;
+    const unsigned myw = t < nseg ? sw[t] : 0u;
+    int rest = differ ? 64 - __clzll((long long)differ) : 0;     // low bits still open
+    unsigned long long prefix = rest == 64 ? 0ull : sel[2] & ~((1ull << rest) - 1ull);
+    unsigned want = (unsigned)R;
+    bool single = false;
+    while (rest > 0) {
+      const int sh = rest > 11 ? rest - 11 : 0;
+      const unsigned mask = (1u << (rest - sh)) - 1u;
+      const unsigned long long hi_mask = rest == 64 ? 0ull : ~((1ull << rest) - 1ull);
+      __syncthreads();
+      bh[t] = 0u; bh[t + 1024] = 0u;
+      bc[t] = 0u; bc[t + 1024] = 0u;
+      __syncthreads();
+      const bool in = myw != 0u && (mykey & hi_mask) == (prefix & hi_mask);
+      const unsigned d = (unsigned)(mykey >> sh) & mask;
+      if (in) { atomicAdd(&bh[d], myw); atomicAdd(&bc[d], 1u); }
+      __syncthreads();
+      const unsigned a1 = bh[2047 - 2 * t], a0 = bh[2046 - 2 * t];
+      const unsigned before = block_scan_u32(a1 + a0, spart);
+      if (before < want && want <= before + a1) { pick32[0] = 2047 - 2 * t; pick32[1] = want - before; }
+      else if (before + a1 < want && want <= before + a1 + a0) { pick32[0] = 2046 - 2 * t; pick32[1] = want - before - a1; }
+      __syncthreads();
+      const unsigned bin = pick32[0];
+      want = pick32[1];
+      prefix |= (unsigned long long)bin << sh;
+      rest = sh;
+      if (bc[bin] == 1u) {
+        // a single segment is left in the chosen bin: its key is g*
+        if (in && d == bin) sel[0] = mykey;
+        single = true;
+        break;
+      }
+    }
+    if (!single && t == 0) sel[0] = prefix;
+    if (t == 0) sel[1] = (unsigned long long)want;
+  } else if (active && wave == 0) {
     const unsigned long long differ = sel[2] ^ sel[3], common = sel[2];
     const bool in_regs = nseg <= 64 * kRegSegs;
     unsigned long long rkey[kRegSegs];
@@ -348,6 +440,22 @@ __device__ inline void alloc_phase_b(const AllocIO& io, int p, char* lds, int ld
       }
     }
     __syncthreads();
+  }
+  if (fast) {
+    // at most 64 heads, sums below 2^31: wave 0 alone, ties in head order by a wave scan
+    if (wave == 0) {
+      const bool live = lane < NH;
+      const unsigned gt = live && active ? (unsigned)h_gt[live ? lane : 0] : 0u;
+      const unsigned eq = live && active ? (unsigned)h_eq[live ? lane : 0] : 0u;
+      const long long eq_before = (long long)(wave_scan_incl(eq) - eq);
+      if (live) {
+        long long take = rem - eq_before;
+        take = take < 0 ? 0 : (take > (long long)eq ? (long long)eq : take);
+        io.budgets[hbase + lane] = (int32_t)(l_lb[lane] + (long long)gt + take);
+      }
+    }
+    if (t == 0) io.status[p] = infeasible ? LUKV_ST_INFEASIBLE : 0;
+    return;
   }
   long long carry = 0;
   for (int h0 = 0; h0 < NH; h0 += nt) {

@@ -8,8 +8,8 @@ __global__ __launch_bounds__(256) void allocate_vertices_kernel(AllocIO io, int 
   alloc_phase_a(io, blockIdx.x / blocks_per_problem, blockIdx.x % blocks_per_problem);
 }
 
-__global__ __launch_bounds__(256) void allocate_budgets_kernel(AllocIO io) {
-  __shared__ __align__(16) char lds[32768];
+__global__ __launch_bounds__(1024) void allocate_budgets_kernel(AllocIO io) {
+  __shared__ __align__(16) char lds[49152];
   alloc_phase_b(io, blockIdx.x, lds, (int)sizeof(lds));
 }
 
@@ -54,7 +54,7 @@ int launch_allocate(const AllocIO& io, hipStream_t st) {
   stage_mark(kStAllocate, st);
   const int bpp = alloc_blocks_a(io.n_heads, io.n_grid);
   hipLaunchKernelGGL(allocate_vertices_kernel, dim3(io.n_problems * bpp), dim3(256), 0, st, io, bpp);
-  hipLaunchKernelGGL(allocate_budgets_kernel, dim3(io.n_problems), dim3(256), 0, st, io);
+  hipLaunchKernelGGL(allocate_budgets_kernel, dim3(io.n_problems), dim3(1024), 0, st, io);
   hipLaunchKernelGGL(offsets_kernel, dim3(1), dim3(256), 0, st, (const int32_t*)io.budgets, io.offsets,
                      (int64_t)io.n_problems * io.n_heads);
   return check_launch();

@@ -109,4 +109,45 @@ __device__ inline void find_tile(const SeqTab& tab, int tile, int& seq, int& loc
   local_tile = tile - tab.tile0[s];
 }
 
+// Inclusive scan over the 64 lanes of a wave with DPP row shifts and row broadcasts (no LDS
+// crossbar traffic): four shifts scan each row of 16 lanes, lane 15 of rows 0 and 2 is then
+// broadcast into rows 1 and 3, and lane 31 into rows 2 and 3.
+__device__ __forceinline__ unsigned wave_scan_incl(unsigned v) {
+  v += (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xf, 0xf, true);   // row_shr:1
+  v += (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xf, 0xf, true);   // row_shr:2
+  v += (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xf, 0xf, true);   // row_shr:4
+  v += (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xf, 0xf, true);   // row_shr:8
+  v += (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xa, 0xf, false);  // row_bcast:15
+  v += (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xc, 0xf, false);  // row_bcast:31
+  return v;
+}
+
+// Reductions over the 64 lanes of a wave with the same DPP steps; the result is valid in lane 63.
+// `ident` is the operation's identity (what a lane without a source contributes).
+template <class Op>
+__device__ __forceinline__ unsigned wave_reduce_to_last(unsigned v, unsigned ident, Op op) {
+  v = op(v, (unsigned)__builtin_amdgcn_update_dpp((int)ident, (int)v, 0x111, 0xf, 0xf, false));
+  v = op(v, (unsigned)__builtin_amdgcn_update_dpp((int)ident, (int)v, 0x112, 0xf, 0xf, false));
+  v = op(v, (unsigned)__builtin_amdgcn_update_dpp((int)ident, (int)v, 0x114, 0xf, 0xf, false));
+  v = op(v, (unsigned)__builtin_amdgcn_update_dpp((int)ident, (int)v, 0x118, 0xf, 0xf, false));
+  v = op(v, (unsigned)__builtin_amdgcn_update_dpp((int)ident, (int)v, 0x142, 0xa, 0xf, false));
+  v = op(v, (unsigned)__builtin_amdgcn_update_dpp((int)ident, (int)v, 0x143, 0xc, 0xf, false));
+  return v;
+}
+
+// Exclusive scan of one unsigned per thread over the workgroup (<= 16 waves); part has 16 slots.
+// Every thread of the workgroup calls it (two barriers inside).  The wave totals are scanned
+// by every wave for itself (one LDS read per lane, no serial chain over the waves).
+__device__ __forceinline__ unsigned block_scan_u32(unsigned v, unsigned* part) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n_waves = blockDim.x >> 6;
+  const unsigned incl = wave_scan_incl(v);
+  __syncthreads();
+  if (lane == 63) part[wave] = incl;
+  __syncthreads();
+  const unsigned tot = lane < n_waves ? part[lane] : 0u;
+  const unsigned upto = wave_scan_incl(tot);
+  const unsigned before_wave = (unsigned)__builtin_amdgcn_readlane((int)(upto - tot), wave);
+  return before_wave + incl - v;
+}
+
 }  // namespace lukv

@@ -66,31 +66,6 @@ struct SelGeom {
   int32_t range_stride;   // entries per head in the range array
 };
 
-// Inclusive scan over the 64 lanes of a wave with DPP row shifts and row broadcasts (no LDS
-// crossbar traffic): four shifts scan each row of 16 lanes, lane 15 of rows 0 and 2 is then
-// broadcast into rows 1 and 3, and lane 31 into rows 2 and 3.
-__device__ __forceinline__ unsigned wave_scan_incl(unsigned v) {
-  v += (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xf, 0xf, true);   // row_shr:1
-  v += (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xf, 0xf, true);   // row_shr:2
-  v += (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xf, 0xf, true);   // row_shr:4
-  v += (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xf, 0xf, true);   // row_shr:8
-  v += (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xa, 0xf, false);  // row_bcast:15
-  v += (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xc, 0xf, false);  // row_bcast:31
-  return v;
-}
-
-// Exclusive scan of one unsigned per thread over the workgroup (<= 16 waves); part has 16 slots.
-__device__ __forceinline__ unsigned scan1024(unsigned v, unsigned* part) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const unsigned incl = wave_scan_incl(v);
-  __syncthreads();
-  if (lane == 63) part[wave] = incl;
-  __syncthreads();
-  unsigned before = incl - v;
-  for (int w = 0; w < wave; ++w) before += part[w];
-  return before;
-}
-
 // (min, max) of the finite scores of every slice, for scores that come from the caller.
 __global__ __launch_bounds__(1024) void sel_range_kernel(SelGeom sg, SeqTab tab, const float* scores,
                                                          float2* range) {
@@ -125,7 +100,7 @@ __global__ __launch_bounds__(1024) void sel_hist_kernel(SelGeom sg, SeqTab tab, 
                                                         float* pooled_out, const float2* range,
                                                         unsigned* hist_parts, uint2* head_dig,
                                                         unsigned long long* by_bin, int32_t* status) {
-  __shared__ __align__(16) char scratch[32768];
+  __shared__ __align__(16) char scratch[49152];
   unsigned* lh = reinterpret_cast<unsigned*>(scratch);                      // kHistBins counters
   float* rawt = reinterpret_cast<float*>(scratch + kHistBins * 4);           // slice + pool halo
   unsigned* part = reinterpret_cast<unsigned*>(scratch + kHistBins * 4 + 4352);
@@ -205,7 +180,7 @@ __global__ __launch_bounds__(1024) void sel_hist_kernel(SelGeom sg, SeqTab tab, 
   __syncthreads();
   // suffix counts, descending bins: thread t owns bins 2047-2t and 2046-2t (packed word 1023-t)
   const unsigned a1 = lh[2047 - 2 * t], a0 = lh[2046 - 2 * t];
-  const unsigned above = scan1024(a1 + a0, part);
+  const unsigned above = block_scan_u32(a1 + a0, part);
   const unsigned s_hi = above + a1, s_lo = s_hi + a0;          // <= 1024: fit 16 bits
   my_part[1023 - t] = s_lo | (s_hi << 16);
   // the slice's (key, position) pairs ordered by descending bin: the keys of bin b sit at
@@ -265,7 +240,7 @@ __device__ __forceinline__ void tail_resolve(List list, unsigned n_c, unsigned w
       }
       __syncthreads();
       const unsigned a1 = lh[2047 - 2 * t], a0 = lh[2046 - 2 * t];
-      const unsigned before = scan1024(a1 + a0, part);
+      const unsigned before = block_scan_u32(a1 + a0, part);
       if (before < want && want <= before + a1) { sel[2] = 2047 - 2 * t; sel[3] = want - before; }
       else if (before + a1 < want && want <= before + a1 + a0) { sel[2] = 2046 - 2 * t; sel[3] = want - before - a1; }
       __syncthreads();
@@ -404,7 +379,7 @@ __global__ __launch_bounds__(1024) void sel_tail_kernel(SelGeom sg, SeqTab tab, 
   if (n_slices <= 64) {
     if (wave == 0) c_off[lane] = wave_scan_incl(n_s) - n_s;
   } else {
-    const unsigned o = scan1024(n_s, part);
+    const unsigned o = block_scan_u32(n_s, part);
     c_off[t] = o;
   }
   __syncthreads();
@@ -432,8 +407,8 @@ __global__ __launch_bounds__(1024) void sel_tail_kernel(SelGeom sg, SeqTab tab, 
   } else {
     const unsigned g = t < n_slices && !keep_none ? s_gt[t] : 0u;
     const unsigned e = t < n_slices && !keep_none ? s_eq[t] : 0u;
-    const unsigned g_before = scan1024(g, part);
-    const unsigned e_before = scan1024(e, part);
+    const unsigned g_before = block_scan_u32(g, part);
+    const unsigned e_before = block_scan_u32(e, part);
     if (t < n_slices) my_cnt[t] = make_uint2(g_before, e_before);
   }
 }
