@@ -250,44 +250,51 @@ __device__ inline void alloc_phase_b(const AllocIO& io, int p, char* lds, int ld
     sum_w += w;
     if (w) { k_and &= key; k_or |= key; }
   }
-  // workgroup sums: every wave reduces its lanes with DPP steps (64-bit values as two halves:
-  // sums of 16-bit pieces of values below 2^32 cannot overflow a lane), then one LDS atomic
-  // per wave and quantity
-  {
+  // workgroup sums.  Small problems: the segments of a head tile (max(b_min, first knot), cap],
+  // so the units on offer and the minimum retention are sums over heads, which wave 0 takes
+  // from LDS; the waves that hold live segments only reduce the AND / OR of their keys (DPP
+  // steps, 64-bit values as two halves), one LDS atomic per wave.
+  if (small && nseg <= nt) {
     auto add = [](unsigned a, unsigned b) { return a + b; };
     auto band = [](unsigned a, unsigned b) { return a & b; };
     auto bor = [](unsigned a, unsigned b) { return a | b; };
-    const bool small_vals = (unsigned long long)sum_min < (1ull << 32) && (unsigned long long)sum_w < (1ull << 32);
-    if (__ballot(!small_vals) == 0ull) {
-      const unsigned m_lo = wave_reduce_to_last((unsigned)sum_min & 0xFFFFu, 0u, add);
-      const unsigned m_hi = wave_reduce_to_last((unsigned)sum_min >> 16, 0u, add);
-      const unsigned w_lo = wave_reduce_to_last((unsigned)sum_w & 0xFFFFu, 0u, add);
-      const unsigned w_hi = wave_reduce_to_last((unsigned)sum_w >> 16, 0u, add);
+    if (wave == 0) {
+      const bool live = lane < NH;
+      const long long lb = live ? l_lb[lane] : 0, cp = live ? l_cp[lane] : 0;
+      const long long n0 = live ? l_kn[lane * Gp] : 0;
+      const bool head_bad = live && (lb < 0 || lb > cp);
+      const long long from = lb > n0 ? lb : n0;
+      const unsigned offer = !head_bad && cp > from ? (unsigned)(cp - from) : 0u;   // < 2^31
+      const unsigned keep = head_bad ? 0u : (unsigned)lb;
+      // sums of 16-bit pieces cannot overflow a lane
+      const unsigned m_lo = wave_reduce_to_last(keep & 0xFFFFu, 0u, add), m_hi = wave_reduce_to_last(keep >> 16, 0u, add);
+      const unsigned w_lo = wave_reduce_to_last(offer & 0xFFFFu, 0u, add), w_hi = wave_reduce_to_last(offer >> 16, 0u, add);
+      const unsigned long long any_bad = __ballot(head_bad);
+      if (lane == 63) {
+        red[0] = (long long)(((unsigned long long)m_hi << 16) + m_lo);
+        red[1] = (long long)(((unsigned long long)w_hi << 16) + w_lo);
+        red[2] = any_bad ? 1 : 0;
+      }
+    }
+    if (__ballot(sum_w != 0) != 0ull) {
       const unsigned a_lo = wave_reduce_to_last((unsigned)k_and, ~0u, band);
       const unsigned a_hi = wave_reduce_to_last((unsigned)(k_and >> 32), ~0u, band);
       const unsigned o_lo = wave_reduce_to_last((unsigned)k_or, 0u, bor);
       const unsigned o_hi = wave_reduce_to_last((unsigned)(k_or >> 32), 0u, bor);
-      const unsigned any_bad = wave_reduce_to_last((unsigned)bad, 0u, bor);
       if (lane == 63) {
-        const unsigned long long wm = ((unsigned long long)m_hi << 16) + m_lo;
-        const unsigned long long ww = ((unsigned long long)w_hi << 16) + w_lo;
-        if (wm) atomicAdd(reinterpret_cast<unsigned long long*>(&red[0]), wm);
-        if (ww) {
-          atomicAdd(reinterpret_cast<unsigned long long*>(&red[1]), ww);
-          atomicAnd(&sel[2], ((unsigned long long)a_hi << 32) | a_lo);
-          atomicOr(&sel[3], ((unsigned long long)o_hi << 32) | o_lo);
-        }
-        if (any_bad) atomicAdd(reinterpret_cast<unsigned long long*>(&red[2]), 1ull);
+        atomicAnd(&sel[2], ((unsigned long long)a_hi << 32) | a_lo);
+        atomicOr(&sel[3], ((unsigned long long)o_hi << 32) | o_lo);
       }
-    } else {
-      if (sum_min) atomicAdd(reinterpret_cast<unsigned long long*>(&red[0]), (unsigned long long)sum_min);
-      if (sum_w) {
-        atomicAdd(reinterpret_cast<unsigned long long*>(&red[1]), (unsigned long long)sum_w);
-        atomicAnd(&sel[2], k_and);
-        atomicOr(&sel[3], k_or);
-      }
-      if (bad) atomicAdd(reinterpret_cast<unsigned long long*>(&red[2]), 1ull);
     }
+  } else {
+    // most threads hold nothing, so only the others touch the LDS counters
+    if (sum_min) atomicAdd(reinterpret_cast<unsigned long long*>(&red[0]), (unsigned long long)sum_min);
+    if (sum_w) {
+      atomicAdd(reinterpret_cast<unsigned long long*>(&red[1]), (unsigned long long)sum_w);
+      atomicAnd(&sel[2], k_and);
+      atomicOr(&sel[3], k_or);
+    }
+    if (bad) atomicAdd(reinterpret_cast<unsigned long long*>(&red[2]), 1ull);
   }
   __syncthreads();
   const long long R = io.B[p] - red[0];

@@ -307,7 +307,7 @@ __global__ __launch_bounds__(256, (F32 && D == 128) ? 1 : 2) void score_accum_ke
 
   if ((int)blockIdx.x < n_alloc_blocks) {
     // a few short extra workgroups: hull vertices of the budget allocation (no use of scores)
-    if (blockIdx.y == 0 && blockIdx.z == 0)
+    if (blockIdx.y == 0 && blockIdx.z == 0 && (int)blockIdx.x / alloc_bpp < aio.n_problems)
       alloc_phase_a(aio, blockIdx.x / alloc_bpp, blockIdx.x % alloc_bpp);
     return;
   }
@@ -335,7 +335,11 @@ __global__ __launch_bounds__(256, (F32 && D == 128) ? 1 : 2) void score_accum_ke
   const int ld_lds = ld_row0 * T::kLdsRowU4 + ld_col;
   const unsigned ld_stride = (unsigned)T::kLoadRowStep * tok_bytes, ld_tile = (unsigned)T::kKeys * tok_bytes;
   const unsigned ld_last = (unsigned)(L - 1) * tok_bytes + (unsigned)ld_col * 16u;
-  unsigned ld_off = (unsigned)(j_begin + ld_row0) * tok_bytes + (unsigned)ld_col * 16u;
+  // Tiles are taken from the last to the first: pass A read them in ascending order, so its
+  // last tile is the one most likely still in the L2 of this XCD when this kernel starts.
+  const int n_tiles = j_end > j_begin ? (j_end - j_begin + T::kKeys - 1) / T::kKeys : 0;
+  const int j_first = j_begin + (n_tiles > 0 ? n_tiles - 1 : 0) * T::kKeys;
+  unsigned ld_off = (unsigned)(j_first + ld_row0) * tok_bytes + (unsigned)ld_col * 16u;
   u32x4 pre[T::kLoads];
   k_issue<F32, D, RG, T::kLoads>(pre, kbase, ld_off, ld_stride, ld_last);
 
@@ -346,7 +350,7 @@ __global__ __launch_bounds__(256, (F32 && D == 128) ? 1 : 2) void score_accum_ke
 
   // Softmax constant of every window row: merge the (max, sum) pairs that pass A left per
   // chunk of this head, c_r = max_r * a + log2(sum_r).  Each thread folds a share of the
-  // chunks of one row, 16 pairs in flight at once; LDS joins the shares.
+  // chunks of one row, 32 pairs in flight at once; LDS joins the shares.
   {
     const int n_chunks = (L + g.chunk_keys - 1) / g.chunk_keys;   // chunks pass A used
     const int nparts = rows_padded >= 256 ? 1 : 256 / rows_padded;
@@ -356,18 +360,18 @@ __global__ __launch_bounds__(256, (F32 && D == 128) ? 1 : 2) void score_accum_ke
       const int r = item % rows_padded, part = item / rows_padded;
       const int c_end = min(n_chunks, (part + 1) * cpp);
       float mm = -INFINITY, zz = 0.f;
-      for (int c0 = part * cpp; c0 < c_end; c0 += 16) {
-        float2 st[16];
+      for (int c0 = part * cpp; c0 < c_end; c0 += 32) {
+        float2 st[32];
 #pragma unroll
-        for (int u = 0; u < 16; ++u)
+        for (int u = 0; u < 32; ++u)
           st[u] = c0 + u < c_end ? hp[(int64_t)(c0 + u) * rows_padded + r] : make_float2(-INFINITY, 0.f);
         float rm = -INFINITY;
 #pragma unroll
-        for (int u = 0; u < 16; ++u) rm = fmaxf(rm, st[u].x);
+        for (int u = 0; u < 32; ++u) rm = fmaxf(rm, st[u].x);
         const float rms = rm == -INFINITY ? 0.f : rm;
         float rz = 0.f;
 #pragma unroll
-        for (int u = 0; u < 16; ++u) rz = fmaf(st[u].y, fast_exp2((st[u].x - rms) * a), rz);
+        for (int u = 0; u < 32; ++u) rz = fmaf(st[u].y, fast_exp2((st[u].x - rms) * a), rz);
         merge_stats(mm, zz, rm, rz, a);
       }
       if (nparts == 1) rowc_s[r] = r < g.rows ? mm * a + log2f(zz) : INFINITY;
@@ -403,12 +407,13 @@ __global__ __launch_bounds__(256, (F32 && D == 128) ? 1 : 2) void score_accum_ke
   float* out = raw + ((int64_t)layer * g.n_kv_heads + kvh) * g.total_tokens + tok0;
   float vmin = INFINITY, vmax = -INFINITY;   // range of the values this lane writes
 
-  for (int j0 = j_begin; j0 < j_end; j0 += T::kKeys) {
+  for (int ti = n_tiles - 1; ti >= 0; --ti) {
+    const int j0 = j_begin + ti * T::kKeys;
     tile_sync<T::kPrivate>();
     k_commit<F32, D, RG, T::kLoads>(pre, ktile, ld_lds);
     tile_sync<T::kPrivate>();
-    ld_off += ld_tile;
-    if (j0 + T::kKeys < j_end) k_issue<F32, D, RG, T::kLoads>(pre, kbase, ld_off, ld_stride, ld_last);
+    ld_off -= ld_tile;
+    if (ti > 0) k_issue<F32, D, RG, T::kLoads>(pre, kbase, ld_off, ld_stride, ld_last);
     const int jw = j0 + 32 * kt;
     float col = 0.f;
     if (jw < j_end) {
@@ -491,7 +496,9 @@ static int launch_raw_t(const HostCfg& hc, const WsLayout& lay, const void* q, c
   AllocIO io;
   memset(&io, 0, sizeof(io));
   int n_alloc = 0, bpp = 1;
-  if (aio) { io = *aio; bpp = alloc_blocks_a(aio->n_heads, aio->n_grid); n_alloc = aio->n_problems * bpp; }
+  // the extra blocks are padded to a multiple of 8 so that a chunk lands on the same XCD (and
+  // its L2) in both passes
+  if (aio) { io = *aio; bpp = alloc_blocks_a(aio->n_heads, aio->n_grid); n_alloc = (aio->n_problems * bpp + 7) / 8 * 8; }
   dim3 gridA(tabA.tile0[tabA.n_seqs], g.n_kv_heads, g.n_layers);
   dim3 gridB(tabB.tile0[tabB.n_seqs] + n_alloc, g.n_kv_heads, g.n_layers);
   stage_mark(kStStats, st);
