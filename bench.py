@@ -42,6 +42,10 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=320)
     ap.add_argument("--warmup", type=int, default=32)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run a plain elementwise pass over 256 MiB (read 256 MiB, write 256 MiB) "
+                         "four times before the warm-up: the known-size kernel that scales the "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE counters (profiles/)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.stderr.write("bench.py: this build runs on ONE GPU only (the path shards without "
@@ -88,6 +92,14 @@ def main() -> int:
         q, k, v = sets[i % N_SETS]
         lukv.lukv_evict(cfg, q, k, v, wl.n_grid, curves, knots, b_min, b_max, B, budgets, offsets,
                         kept, k_out, v_out, None, status, ws)
+
+    if args.calibration_copy:
+        src = torch.zeros(64 * 1024 * 1024, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            torch.add(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- timed region: W warm-up steps, then exactly K steps --------------------------------
     for i in range(args.warmup):
@@ -146,8 +158,18 @@ def main() -> int:
     # whole-step algorithmic traffic (streaming model): K twice, Q, scores w+r, idx w+r,
     # gather reads of kept K and V rows, compacted K and V writes
     b_alg = 2 * k_bytes + q_bytes + 2 * Hkv * L * 4 + 2 * rows * 4 + 2 * rows * d * esz + 2 * rows * d * esz
+    # measured HBM bytes per launch of that kernel: rocprofv3 counter runs of this same command,
+    # scaled by the calibration copy, stored beside their summaries (None if not measured)
+    traffic, traffic_detail = None, None
+    tpath = os.path.join(ROOT, "profiles", "lukv_evict_8b_32k_hbm_traffic.json")
+    if os.path.exists(tpath):
+        rec = json.load(open(tpath)).get(dom)
+        if rec:
+            traffic = rec["fetch_bytes"] + rec["write_bytes"]
+            traffic_detail = rec
     roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+                "traffic_detail": traffic_detail,
                 "alg_bytes_per_launch": alg[dom], "kernel_us": stages[dom],
                 "step_alg_bytes": b_alg,
                 "step_frac_of_hbm": round(b_alg / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
