@@ -45,7 +45,7 @@ def decode(x: np.ndarray) -> np.ndarray:
 # ----------------------------------------------------------------------------
 
 def window_attention_sum(q_win: np.ndarray, k: np.ndarray, n_kv_heads: int,
-                         scale: float | None = None) -> np.ndarray:
+                         scale: float | None = None, lse: np.ndarray | None = None) -> np.ndarray:
     """Unpooled metric: for every KV head, the attention mass each cached position
     receives from the last w queries, summed over the window and averaged over the
     G query heads that share the KV head.
@@ -56,6 +56,11 @@ def window_attention_sum(q_win: np.ndarray, k: np.ndarray, n_kv_heads: int,
     Readings: window row i sits at position L-w+i and sees keys j <= L-w+i (Eq. 1's
     j <= k); the sum (not mean) over the window ("accumulated attention scores");
     mean over the group's query heads, taken before pooling.
+
+    lse [H_q, w] (optional): the log of Eq. 1's denominator for every window row, as a
+    prefill attention kernel leaves it (natural log of the sum over the visible keys of
+    exp(scaled logit)).  When given it is used as the normaliser, A = exp(s - lse), instead
+    of being recomputed (Sec. 4.3: the scores are a by-product of prefill).
     """
     H_q, w, d = q_win.shape
     H_kv, L, _ = k.shape
@@ -71,9 +76,12 @@ def window_attention_sum(q_win: np.ndarray, k: np.ndarray, n_kv_heads: int,
         for g in range(G):
             s = scale * (q_win[c * G + g] @ k[c].T)    # [w, L]
             s = np.where(visible, s, -np.inf)
-            m = s.max(axis=1, keepdims=True)
-            e = np.exp(s - m)
-            p = e / e.sum(axis=1, keepdims=True)
+            if lse is not None:
+                p = np.exp(s - np.asarray(lse[c * G + g], dtype=np.float64)[:, None])
+            else:
+                m = s.max(axis=1, keepdims=True)
+                e = np.exp(s - m)
+                p = e / e.sum(axis=1, keepdims=True)
             acc += p.sum(axis=0)
         out[c] = acc / G
     return out
@@ -92,8 +100,29 @@ def max_pool_1d(r: np.ndarray, kernel: int) -> np.ndarray:
     return out
 
 
+def window_lse(q_win: np.ndarray, k: np.ndarray, n_kv_heads: int,
+               scale: float | None = None) -> np.ndarray:
+    """log of Eq. 1's denominator for every window row: lse[q, i] = log sum_{j <= L-w+i}
+    exp(scale * q_i . k_j), float64 [H_q, w].  What a prefill attention kernel returns
+    beside its output; an INPUT of the lse variant of the score step."""
+    H_q, w, d = q_win.shape
+    H_kv, L, _ = k.shape
+    G = H_q // n_kv_heads
+    if scale is None:
+        scale = 1.0 / math.sqrt(d)
+    out = np.zeros((H_q, w), dtype=np.float64)
+    for qh in range(H_q):
+        s = scale * (q_win[qh] @ k[qh // G].T)
+        for i in range(w):
+            row = s[i, :L - w + i + 1]
+            m = row.max()
+            out[qh, i] = m + math.log(np.exp(row - m).sum())
+    return out
+
+
 def score(q_win: np.ndarray, k: np.ndarray, n_kv_heads: int, window: int,
-          pool_kernel: int, n_sink: int, scale: float | None = None) -> np.ndarray:
+          pool_kernel: int, n_sink: int, scale: float | None = None,
+          lse: np.ndarray | None = None) -> np.ndarray:
     """Pooled SnapKV score S [H_kv, L] float32.
 
     The window sum is pooled over the prefix [0, L-w) only; the result is rounded to
@@ -104,7 +133,7 @@ def score(q_win: np.ndarray, k: np.ndarray, n_kv_heads: int, window: int,
     P = L - window
     if P < 1:
         raise ValueError("context must be longer than the observation window")
-    r = window_attention_sum(q_win, k, n_kv_heads, scale)
+    r = window_attention_sum(q_win, k, n_kv_heads, scale, lse)
     s = np.full(r.shape, np.inf, dtype=np.float32)
     s[:, :P] = max_pool_1d(r[:, :P], pool_kernel).astype(np.float32)
     s[:, :min(n_sink, L)] = np.inf
@@ -219,13 +248,15 @@ def compact(x: np.ndarray, idx: np.ndarray) -> np.ndarray:
 def evict(q_win: np.ndarray, k: np.ndarray, v: np.ndarray, cu_seqlens: Sequence[int],
           n_kv_heads: int, window: int, pool_kernel: int, n_sink: int,
           curves: np.ndarray, knots: np.ndarray, b_min: np.ndarray, b_max: np.ndarray,
-          B: Sequence[int], layers: Sequence[int] | None = None, scale: float | None = None):
+          B: Sequence[int], layers: Sequence[int] | None = None, scale: float | None = None,
+          lse: np.ndarray | None = None):
     """score -> allocate -> select -> compact for packed sequences.
 
     q_win [NL, H_q, n_seqs*w, d], k, v [NL, H_kv, total_len, d] as stored (bf16 bits or
     f32); curves/knots [n_seqs, NL*H_kv, Gp]; b_min/b_max [n_seqs, NL*H_kv]; B [n_seqs].
     Heads are ordered (sequence, layer, kv head).  `layers` restricts scoring/selection to
     some layers (allocation is always global); other layers get empty outputs.
+    lse [NL, H_q, n_seqs*w] float32 (optional): the window rows' log-sum-exp, see score().
 
     Returns dict: budgets [n_seqs*NL*H_kv], offsets [..+1], status [n_seqs],
     pooled {(s, l): [H_kv, L_s] f32}, kept {(s, l, c): int32 idx}, k_out/v_out {(s,l,c): rows}.
@@ -246,7 +277,8 @@ def evict(q_win: np.ndarray, k: np.ndarray, v: np.ndarray, cu_seqlens: Sequence[
         for l in use_layers:
             q = decode(q_win[l, :, s * window:(s + 1) * window, :])
             kk = decode(k[l, :, a:b, :])
-            S = score(q, kk, n_kv_heads, window, pool_kernel, n_sink, scale)
+            row_lse = None if lse is None else lse[l, :, s * window:(s + 1) * window]
+            S = score(q, kk, n_kv_heads, window, pool_kernel, n_sink, scale, row_lse)
             pooled[(s, l)] = S
             for c in range(n_kv_heads):
                 hi = (s * NL + l) * n_kv_heads + c

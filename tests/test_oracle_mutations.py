@@ -14,7 +14,7 @@ from oracle import lukv_oracle as O
 from tests import test_oracle_allocate as TA
 from tests import test_oracle_score as TS
 
-PUBLIC = ["window_attention_sum", "max_pool_1d", "score", "concave_hull", "marginal_gains",
+PUBLIC = ["window_attention_sum", "window_lse", "max_pool_1d", "score", "concave_hull", "marginal_gains",
           "_gain_of_unit", "_slope", "allocate", "select", "compact", "offsets_of"]
 
 MUTANTS = {
@@ -27,7 +27,7 @@ MUTANTS = {
                                lambda: TS.test_identical_keys_closed_form_and_group_mean()),
     "mean_over_window": ("acc += p.sum(axis=0)", "acc += p.mean(axis=0)",
                          lambda: TS.test_total_mass_is_window_size()),
-    "missing_scale": ("scale = 1.0 / math.sqrt(d)", "scale = 1.0",
+    "missing_scale": ("scale = 1.0 / math.sqrt(d)\n    out = np.zeros((H_kv, L)", "scale = 1.0\n    out = np.zeros((H_kv, L)",
                       lambda: TS.test_brute_force_definition()),
     "softmax_over_queries": ("p = e / e.sum(axis=1, keepdims=True)",
                              "p = e / e.sum(axis=0, keepdims=True)",
@@ -39,6 +39,12 @@ MUTANTS = {
     "pool_over_window_too": ("s[:, :P] = max_pool_1d(r[:, :P], pool_kernel)",
                              "s[:, :P] = max_pool_1d(r, pool_kernel)[:, :P]",
                              lambda: TS.test_handworked_pool_stays_inside_prefix()),
+    "lse_added_not_subtracted": ("p = np.exp(s - np.asarray(lse[c * G + g]", "p = np.exp(s + np.asarray(lse[c * G + g]",
+                                 lambda: TS.test_handworked_lse_variant()),
+    "lse_of_wrong_head": ("p = np.exp(s - np.asarray(lse[c * G + g]", "p = np.exp(s - np.asarray(lse[c + g]",
+                          lambda: TS.test_lse_variant_equals_recomputed_normaliser()),
+    "lse_not_causal": ("row = s[i, :L - w + i + 1]", "row = s[i, :]",
+                       lambda: TS.test_handworked_lse_variant()),
     "sink_not_forced": ("s[:, :min(n_sink, L)] = np.inf", "pass",
                         lambda: TS.test_brute_force_definition()),
     "hull_keeps_collinear": ("if steepness_in > steepness_out:", "if steepness_in >= steepness_out:",

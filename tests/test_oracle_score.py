@@ -63,6 +63,37 @@ def test_handworked_pool_stays_inside_prefix():
     assert np.array_equal(s[0][:4], want[:4].astype(np.float32))
 
 
+def test_handworked_lse_variant():
+    g, q, k = _handworked_inputs()
+    lse = np.log(np.array(g["row_sums"]))[None, :]
+    assert np.allclose(O.window_lse(q, k, 1, scale=1.0), lse, rtol=1e-15)
+    r = O.window_attention_sum(q, k, 1, scale=1.0, lse=lse)
+    assert np.allclose(r[0, :4], g["unpooled"], rtol=0, atol=1e-14)
+    # a normaliser that is too large by ln 2 halves every probability
+    r2 = O.window_attention_sum(q, k, 1, scale=1.0, lse=lse + math.log(2.0))
+    assert np.allclose(r2[0, :4], np.array(g["unpooled"]) / 2, rtol=1e-14)
+
+
+def test_lse_variant_equals_recomputed_normaliser():
+    L, w, d, Hq, Hkv = 77, 6, 8, 6, 3
+    rng = np.random.default_rng(11)
+    q = rng.standard_normal((Hq, w, d)) * 2
+    k = rng.standard_normal((Hkv, L, d))
+    lse = O.window_lse(q, k, Hkv)
+    # brute-force definition of the log-sum-exp
+    for qh in (0, 5):
+        for i in (0, w - 1):
+            t = L - w + i
+            want = math.log(sum(math.exp(sum(q[qh, i, x] * k[qh // 2, j, x] for x in range(d)) / math.sqrt(d))
+                                for j in range(t + 1)))
+            assert lse[qh, i] == pytest.approx(want, rel=1e-13)
+    a = O.score(q, k, Hkv, w, 5, 2)
+    b = O.score(q, k, Hkv, w, 5, 2, lse=lse)
+    fin = np.isfinite(a)
+    assert np.array_equal(fin, np.isfinite(b))
+    assert np.allclose(a[fin], b[fin], rtol=1e-6)
+
+
 def test_handworked_topk_lowest_index_ties():
     g, q, k = _handworked_inputs()
     s = O.score(q, k, 1, window=2, pool_kernel=3, n_sink=0, scale=1.0)
