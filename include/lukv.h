@@ -140,6 +140,23 @@ int lukv_evict(const lukv_config* cfg, const void* q_win, const void* k, const v
                void* k_out, void* v_out, float* pooled, int32_t* status,
                void* ws, int64_t ws_bytes, void* stream);
 
+/* Variants of lukv_score and lukv_evict for callers whose prefill attention kernel already
+ * leaves the log of Eq. 1's denominator for the window rows (Sec. 4.3: the observation-window
+ * scores are a by-product of prefill): the pass over K that recomputes the softmax statistics is
+ * skipped and probabilities are exp(scale * q.k - lse).
+ *   lse device float32 [n_layers][n_q_heads][n_seqs * window], contiguous: natural log of the sum
+ *       over the visible keys (0 .. L-w+i for window row i) of exp(softmax_scale * q.k).
+ * Everything else as in lukv_score / lukv_evict.  A wrong lse scales that row's contribution; it
+ * is not checked. */
+int lukv_score_lse(const lukv_config* cfg, const void* q_win, const void* k, const float* lse,
+                   float* pooled, void* ws, int64_t ws_bytes, void* stream);
+int lukv_evict_lse(const lukv_config* cfg, const void* q_win, const void* k, const void* v,
+                   const float* lse, int32_t n_grid, const float* curves, const int32_t* knots,
+                   const int32_t* b_min, const int32_t* b_max, const int64_t* B_total,
+                   int32_t* budgets, int64_t* offsets, int32_t* kept_idx,
+                   void* k_out, void* v_out, float* pooled, int32_t* status,
+                   void* ws, int64_t ws_bytes, void* stream);
+
 /* Instrumentation for benchmarks (process-wide, not thread-safe; for callers that time the path,
  * not part of the method).  While n_events > 0, every call records events[i] (hipEvent_t, created
  * by the caller, passed as void*) on its stream immediately before stage i, and lukv_evict records

@@ -162,8 +162,8 @@ int lukv_allocate_workspace_bytes(int32_t n_problems, int32_t n_heads, int32_t n
   return LUKV_OK;
 }
 
-int lukv_score(const lukv_config* cfg, const void* q_win, const void* k, float* pooled,
-               void* ws, int64_t ws_bytes, void* stream) {
+static int score_impl(const lukv_config* cfg, const void* q_win, const void* k, const float* lse,
+                      float* pooled, void* ws, int64_t ws_bytes, void* stream) {
   HostCfg hc;
   int rc = validate_config(cfg, &hc);
   if (rc) return rc;
@@ -171,8 +171,19 @@ int lukv_score(const lukv_config* cfg, const void* q_win, const void* k, float* 
   const WsLayout lay = make_layout(hc, 0, false);
   if ((rc = check_ws(lay, ws, ws_bytes))) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  if ((rc = launch_score_raw(hc, lay, q_win, k, nullptr, (char*)ws, st))) return rc;
+  if ((rc = launch_score_raw(hc, lay, q_win, k, lse, nullptr, (char*)ws, st))) return rc;
   return launch_pool(hc, lay, pooled, (char*)ws, st);
+}
+
+int lukv_score(const lukv_config* cfg, const void* q_win, const void* k, float* pooled,
+               void* ws, int64_t ws_bytes, void* stream) {
+  return score_impl(cfg, q_win, k, nullptr, pooled, ws, ws_bytes, stream);
+}
+
+int lukv_score_lse(const lukv_config* cfg, const void* q_win, const void* k, const float* lse,
+                   float* pooled, void* ws, int64_t ws_bytes, void* stream) {
+  if (!lse) return LUKV_EINVAL;
+  return score_impl(cfg, q_win, k, lse, pooled, ws, ws_bytes, stream);
 }
 
 int lukv_allocate(int32_t n_problems, int32_t n_heads, int32_t n_grid, const float* curves,
@@ -215,7 +226,8 @@ int lukv_select_compact(const lukv_config* cfg, const float* pooled, const int32
                                false, k, v, kept_idx, k_out, v_out, out_rows, status, (char*)ws, st);
 }
 
-int lukv_evict(const lukv_config* cfg, const void* q_win, const void* k, const void* v,
+static int evict_impl(const lukv_config* cfg, const void* q_win, const void* k, const void* v,
+               const float* lse,
                int32_t n_grid, const float* curves, const int32_t* knots, const int32_t* b_min,
                const int32_t* b_max, const int64_t* B_total, int32_t* budgets, int64_t* offsets,
                int32_t* kept_idx, void* k_out, void* v_out, float* pooled, int32_t* status,
@@ -246,11 +258,30 @@ int lukv_evict(const lukv_config* cfg, const void* q_win, const void* k, const v
   const int n_heads = hc.g.n_layers * hc.g.n_kv_heads;
   const AllocIO aio = make_alloc_io(cfg->n_seqs, n_heads, n_grid, curves, knots, b_min, b_max, B_total,
                                     budgets, offsets, status, lay, w);
-  if ((rc = launch_score_raw(hc, lay, q_win, k, &aio, w, st))) return rc;
+  if ((rc = launch_score_raw(hc, lay, q_win, k, lse, &aio, w, st))) return rc;
   rc = launch_select_compact(hc, lay, &aio, reinterpret_cast<const float*>(w + lay.raw), true, scores, budgets,
                              offsets, true, k, v, kept_idx, k_out, v_out, out_rows, sel_status, w, st);
   stage_mark(kStEnd, st);
   return rc;
+}
+
+int lukv_evict(const lukv_config* cfg, const void* q_win, const void* k, const void* v,
+               int32_t n_grid, const float* curves, const int32_t* knots, const int32_t* b_min,
+               const int32_t* b_max, const int64_t* B_total, int32_t* budgets, int64_t* offsets,
+               int32_t* kept_idx, void* k_out, void* v_out, float* pooled, int32_t* status,
+               void* ws, int64_t ws_bytes, void* stream) {
+  return evict_impl(cfg, q_win, k, v, nullptr, n_grid, curves, knots, b_min, b_max, B_total, budgets,
+                    offsets, kept_idx, k_out, v_out, pooled, status, ws, ws_bytes, stream);
+}
+
+int lukv_evict_lse(const lukv_config* cfg, const void* q_win, const void* k, const void* v,
+                   const float* lse, int32_t n_grid, const float* curves, const int32_t* knots,
+                   const int32_t* b_min, const int32_t* b_max, const int64_t* B_total,
+                   int32_t* budgets, int64_t* offsets, int32_t* kept_idx, void* k_out, void* v_out,
+                   float* pooled, int32_t* status, void* ws, int64_t ws_bytes, void* stream) {
+  if (!lse) return LUKV_EINVAL;
+  return evict_impl(cfg, q_win, k, v, lse, n_grid, curves, knots, b_min, b_max, B_total, budgets,
+                    offsets, kept_idx, k_out, v_out, pooled, status, ws, ws_bytes, stream);
 }
 
 int lukv_set_stage_events(void* const* events, int32_t n_events) {

@@ -77,8 +77,9 @@ SeqTab tiles_for(const SeqTab& seq, int tile, int shrink);  // tiles over (L_s -
 struct AllocIO;
 // raw (unpooled) metric into the workspace; aio != NULL: the allocation's first phase rides
 // along in the second score kernel
+// lse != NULL: the window rows' log-sum-exp is given, pass A is not launched
 int launch_score_raw(const HostCfg& hc, const WsLayout& lay, const void* q, const void* k,
-                     const AllocIO* aio, char* ws, hipStream_t st);
+                     const float* lse, const AllocIO* aio, char* ws, hipStream_t st);
 int launch_pool(const HostCfg& hc, const WsLayout& lay, float* pooled_out, char* ws, hipStream_t st);
 // aio != NULL: the allocation's second phase rides along in the first selection kernel
 int launch_select_compact(const HostCfg& hc, const WsLayout& lay, const AllocIO* aio,

@@ -296,6 +296,7 @@ __global__ __launch_bounds__(256, (F32 && D == 128) ? 1 : 2) void score_accum_ke
                                                           int n_alloc_blocks, int alloc_bpp,
                                                           const char* q,
                                                           const char* k, const float2* partial,
+                                                          const float* lse,
                                                           float* raw, float2* range, int max_chunks,
                                                           int rows_padded) {
   using T = Tile<F32, D, RG>;
@@ -348,10 +349,20 @@ __global__ __launch_bounds__(256, (F32 && D == 128) ? 1 : 2) void score_accum_ke
   u32x4 qtmp[QStage<F32, D, NBM>::kLoads];
   q_fetch<F32, D, NBM, QStage<F32, D, NBM>::kLoads>(qtmp, g, q, layer, kvh, seq, 0);
 
-  // Softmax constant of every window row: merge the (max, sum) pairs that pass A left per
-  // chunk of this head, c_r = max_r * a + log2(sum_r).  Each thread folds a share of the
-  // chunks of one row, 32 pairs in flight at once; LDS joins the shares.
-  {
+  // Softmax constant of every window row, c_r = log2 of the row's denominator.  Either the
+  // caller's log-sum-exp (row r = query head r / w of the group, window row r % w), or the merge
+  // of the (max, sum) pairs that pass A left per chunk of this head, c_r = max_r * a + log2(sum_r):
+  // each thread folds a share of the chunks of one row, 32 pairs in flight at once; LDS joins
+  // the shares.
+  if (lse) {
+    const int64_t qh0 = (int64_t)layer * g.n_q_heads + (int64_t)kvh * g.group;
+    const int64_t row_len = (int64_t)tab.n_seqs * g.window;
+    for (int r = threadIdx.x; r < kMaxRows; r += 256) {
+      float c = INFINITY;   // padded rows never contribute
+      if (r < g.rows) c = lse[(qh0 + r / g.window) * row_len + (int64_t)seq * g.window + r % g.window] * 1.44269504088896340736f;
+      rowc_s[r] = c;
+    }
+  } else {
     const int n_chunks = (L + g.chunk_keys - 1) / g.chunk_keys;   // chunks pass A used
     const int nparts = rows_padded >= 256 ? 1 : 256 / rows_padded;
     const int cpp = (n_chunks + nparts - 1) / nparts;
@@ -486,7 +497,7 @@ __global__ __launch_bounds__(256) void pool_kernel(Geom g, SeqTab tab, const flo
 // ---- launchers ---------------------------------------------------------------------------
 template <bool F32, int D, int NBM, int RG>
 static int launch_raw_t(const HostCfg& hc, const WsLayout& lay, const void* q, const void* k,
-                        const AllocIO* aio, char* ws, hipStream_t st) {
+                        const float* lse, const AllocIO* aio, char* ws, hipStream_t st) {
   const Geom& g = hc.g;
   float2* partial = reinterpret_cast<float2*>(ws + lay.partial);
   float* raw = reinterpret_cast<float*>(ws + lay.raw);
@@ -502,34 +513,35 @@ static int launch_raw_t(const HostCfg& hc, const WsLayout& lay, const void* q, c
   dim3 gridA(tabA.tile0[tabA.n_seqs], g.n_kv_heads, g.n_layers);
   dim3 gridB(tabB.tile0[tabB.n_seqs] + n_alloc, g.n_kv_heads, g.n_layers);
   stage_mark(kStStats, st);
-  hipLaunchKernelGGL((score_stats_kernel<F32, D, NBM, RG>), gridA, dim3(256), 0, st, g, tabA,
-                     (const char*)q, (const char*)k, partial, lay.max_chunks,
-                     lay.rows_padded);
+  if (!lse)
+    hipLaunchKernelGGL((score_stats_kernel<F32, D, NBM, RG>), gridA, dim3(256), 0, st, g, tabA,
+                       (const char*)q, (const char*)k, partial, lay.max_chunks,
+                       lay.rows_padded);
   stage_mark(kStAccum, st);
   hipLaunchKernelGGL((score_accum_kernel<F32, D, NBM, RG>), gridB, dim3(256), 0, st, g, tabB, io,
-                     n_alloc, bpp, (const char*)q, (const char*)k, (const float2*)partial, raw,
+                     n_alloc, bpp, (const char*)q, (const char*)k, (const float2*)partial, lse, raw,
                      range, lay.max_chunks, lay.rows_padded);
   return check_launch();
 }
 
 template <bool F32, int D, int NBM>
 static int launch_raw_rg(const HostCfg& hc, const WsLayout& lay, const void* q, const void* k,
-                         const AllocIO* aio, char* ws, hipStream_t st) {
+                         const float* lse, const AllocIO* aio, char* ws, hipStream_t st) {
   switch (hc.g.row_groups) {
-    case 1: return launch_raw_t<F32, D, NBM, 1>(hc, lay, q, k, aio, ws, st);
-    case 2: return launch_raw_t<F32, D, NBM, 2>(hc, lay, q, k, aio, ws, st);
-    case 4: return launch_raw_t<F32, D, NBM, 4>(hc, lay, q, k, aio, ws, st);
+    case 1: return launch_raw_t<F32, D, NBM, 1>(hc, lay, q, k, lse, aio, ws, st);
+    case 2: return launch_raw_t<F32, D, NBM, 2>(hc, lay, q, k, lse, aio, ws, st);
+    case 4: return launch_raw_t<F32, D, NBM, 4>(hc, lay, q, k, lse, aio, ws, st);
   }
   return LUKV_EINVAL;
 }
 
 int launch_score_raw(const HostCfg& hc, const WsLayout& lay, const void* q, const void* k,
-                     const AllocIO* aio, char* ws, hipStream_t st) {
+                     const float* lse, const AllocIO* aio, char* ws, hipStream_t st) {
   const Geom& g = hc.g;
-  if (!g.f32 && g.head_dim == 128) return launch_raw_rg<false, 128, 4>(hc, lay, q, k, aio, ws, st);
-  if (!g.f32 && g.head_dim == 64) return launch_raw_rg<false, 64, 4>(hc, lay, q, k, aio, ws, st);
-  if (g.f32 && g.head_dim == 64) return launch_raw_rg<true, 64, 4>(hc, lay, q, k, aio, ws, st);
-  if (g.f32 && g.head_dim == 128) return launch_raw_rg<true, 128, 2>(hc, lay, q, k, aio, ws, st);
+  if (!g.f32 && g.head_dim == 128) return launch_raw_rg<false, 128, 4>(hc, lay, q, k, lse, aio, ws, st);
+  if (!g.f32 && g.head_dim == 64) return launch_raw_rg<false, 64, 4>(hc, lay, q, k, lse, aio, ws, st);
+  if (g.f32 && g.head_dim == 64) return launch_raw_rg<true, 64, 4>(hc, lay, q, k, lse, aio, ws, st);
+  if (g.f32 && g.head_dim == 128) return launch_raw_rg<true, 128, 2>(hc, lay, q, k, lse, aio, ws, st);
   return LUKV_EDTYPE;
 }
 

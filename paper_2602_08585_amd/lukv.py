@@ -32,8 +32,8 @@ LUKV_ST_INFEASIBLE = 1
 LUKV_ST_CLAMPED = 2
 
 EXPORTS = ("lukv_workspace_bytes", "lukv_allocate_workspace_bytes", "lukv_score", "lukv_allocate",
-           "lukv_select_compact", "lukv_evict", "lukv_set_stage_events", "lukv_stage_name",
-           "lukv_strerror")
+           "lukv_select_compact", "lukv_evict", "lukv_score_lse", "lukv_evict_lse",
+           "lukv_set_stage_events", "lukv_stage_name", "lukv_strerror")
 LUKV_STAGE_END = 7
 LUKV_NUM_STAGE_EVENTS = 8
 
@@ -77,6 +77,9 @@ def load_library() -> ctypes.CDLL:
     lib.lukv_select_compact.argtypes = [CP, P, P, P, P, P, I64, P, P, P, P, P, I64, P]
     lib.lukv_evict.argtypes = [CP, P, P, P, I32, P, P, P, P, ctypes.POINTER(I64),
                                P, P, P, P, P, P, P, P, I64, P]
+    lib.lukv_score_lse.argtypes = [CP, P, P, P, P, P, I64, P]
+    lib.lukv_evict_lse.argtypes = [CP, P, P, P, P, I32, P, P, P, P, ctypes.POINTER(I64),
+                                   P, P, P, P, P, P, P, P, I64, P]
     lib.lukv_set_stage_events.argtypes = [ctypes.POINTER(ctypes.c_void_p), I32]
     lib.lukv_stage_name.argtypes = [I32]
     lib.lukv_stage_name.restype = ctypes.c_char_p
@@ -114,6 +117,11 @@ class Config:
     softmax_scale: float = 0.0
 
     def to_c(self):
+        """The C struct for this configuration (built once and reused: a Config is not meant to be
+        mutated after its first use)."""
+        cached = self.__dict__.get("_c")
+        if cached is not None:
+            return cached
         cu = (ctypes.c_int32 * len(self.cu_seqlens))(*[int(x) for x in self.cu_seqlens])
         c = _CConfig(self.n_layers, self.n_q_heads, self.n_kv_heads, self.head_dim, self.window,
                      self.pool_kernel, self.n_sink, self.dtype, len(self.cu_seqlens) - 1,
@@ -121,6 +129,7 @@ class Config:
                      self.stride_head, self.stride_tok, self.qstride_layer, self.qstride_head,
                      self.qstride_tok, self.softmax_scale)
         c._keepalive = cu
+        self.__dict__["_c"] = c
         return c
 
     @property
@@ -194,6 +203,12 @@ def lukv_score(cfg: Config, q_win, k, pooled, ws, stream=None) -> None:
                                      _ptr(ws), ws.numel(), _stream(stream)), "lukv_score")
 
 
+def lukv_score_lse(cfg: Config, q_win, k, lse, pooled, ws, stream=None) -> None:
+    _check(load_library().lukv_score_lse(ctypes.byref(cfg.to_c()), _ptr(q_win), _ptr(k), _ptr(lse),
+                                         _ptr(pooled), _ptr(ws), ws.numel(), _stream(stream)),
+           "lukv_score_lse")
+
+
 def lukv_allocate(n_problems: int, n_heads: int, n_grid: int, curves, knots, b_min, b_max,
                   B_total: Sequence[int], budgets, offsets, status, ws, stream=None) -> None:
     keep, Bp = _host_i64(B_total)
@@ -221,6 +236,18 @@ def lukv_evict(cfg: Config, q_win, k, v, n_grid: int, curves, knots, b_min, b_ma
                                      _ptr(budgets), _ptr(offsets), _ptr(kept_idx), _ptr(k_out),
                                      _ptr(v_out), _ptr(pooled), _ptr(status), _ptr(ws), ws.numel(),
                                      _stream(stream)), "lukv_evict")
+
+
+def lukv_evict_lse(cfg: Config, q_win, k, v, lse, n_grid: int, curves, knots, b_min, b_max,
+                   B_total: Sequence[int], budgets, offsets, kept_idx, k_out, v_out, pooled, status,
+                   ws, stream=None) -> None:
+    keep, Bp = _host_i64(B_total)
+    _check(load_library().lukv_evict_lse(ctypes.byref(cfg.to_c()), _ptr(q_win), _ptr(k), _ptr(v),
+                                         _ptr(lse), n_grid, _ptr(curves), _ptr(knots), _ptr(b_min),
+                                         _ptr(b_max), Bp, _ptr(budgets), _ptr(offsets),
+                                         _ptr(kept_idx), _ptr(k_out), _ptr(v_out), _ptr(pooled),
+                                         _ptr(status), _ptr(ws), ws.numel(), _stream(stream)),
+           "lukv_evict_lse")
 
 
 def lukv_set_stage_events(events) -> None:

@@ -72,11 +72,34 @@ class Problem:
         torch.cuda.synchronize()
         return out
 
-    def oracle(self, layers=None):
+    def oracle(self, layers=None, lse=None):
         wl, a = self.wl, self.alloc
         return O.evict(self.data["q_win"], self.data["k"], self.data["v"], wl.cu_seqlens,
                        wl.n_kv_heads, wl.window, wl.pool_kernel, wl.n_sink, a["curves"], a["knots"],
-                       a["b_min"], a["b_max"], a["B"], layers=layers)
+                       a["b_min"], a["b_max"], a["B"], layers=layers, lse=lse)
+
+    def oracle_lse(self):
+        """The window rows' log-sum-exp as the oracle computes it (fp64, rounded to fp32):
+        [NL, H_q, n_seqs*w], the extra INPUT of the lse variants."""
+        wl = self.wl
+        q, k = self.data["q_win"], self.data["k"]
+        out = np.zeros((q.shape[0], wl.n_q_heads, wl.n_seqs * wl.window), np.float32)
+        cu = wl.cu_seqlens
+        for l in range(q.shape[0]):
+            for s in range(wl.n_seqs):
+                sl = slice(s * wl.window, (s + 1) * wl.window)
+                out[l, :, sl] = O.window_lse(O.decode(q[l, :, sl, :]), O.decode(k[l, :, cu[s]:cu[s + 1], :]),
+                                             wl.n_kv_heads)
+        return out
+
+    def evict_lse(self, lse, out=None, with_pooled=True):
+        out = self.new_outputs() if out is None else out
+        lukv.lukv_evict_lse(self.cfg, self.q, self.k, self.v, lse, self.wl.n_grid, self.curves,
+                            self.knots, self.b_min, self.b_max, self.B, out["budgets"], out["offsets"],
+                            out["kept_idx"], out["k_out"], out["v_out"],
+                            out["pooled"] if with_pooled else None, out["status"], self.ws)
+        torch.cuda.synchronize()
+        return out
 
 
 def assert_scores_close(got: np.ndarray, want: np.ndarray, rtol=1e-3):

@@ -142,6 +142,27 @@ def test_evict_fused_parity(name):
         assert n_band == 0
 
 
+@pytest.mark.parametrize("name", ["tiny", "bf16_g4_w32", "bf16_g5_w32", "bf16_ragged", "f32_d64_peaky"])
+def test_lse_variant_parity(name):
+    """Scores and the fused path with the window rows' log-sum-exp supplied (no statistics pass)."""
+    print("case", name, flush=True)
+    p = _problem(name)
+    wl = p.wl
+    lse_h = p.oracle_lse()
+    lse = dev(lse_h)
+    ref = p.oracle(lse=lse_h)
+    pooled = torch.full((wl.n_layers, wl.n_kv_heads, wl.total_len), float("nan"), dtype=torch.float32,
+                        device="cuda")
+    lukv.lukv_score_lse(p.cfg, p.q, p.k, lse, pooled, p.ws)
+    torch.cuda.synchronize()
+    got = pooled.cpu().numpy()
+    cu = wl.cu_seqlens
+    for (s, l), S in ref["pooled"].items():
+        assert_scores_close(got[l, :, cu[s]:cu[s + 1]], S)
+    out = p.evict_lse(lse)
+    _check_evict(p, out, ref)
+
+
 def test_evict_is_deterministic_and_pooled_optional():
     p = _problem("bf16_ragged")
     a = p.evict()
