@@ -383,3 +383,80 @@ def test_evict_full_size_8b_32k():
     assert np.array_equal(out2["kept_idx"].cpu().numpy(), want_idx)
     want_k = np.concatenate([ref["k_out"][(0, 0, c)] for c in range(wl.n_kv_heads)])
     assert np.array_equal(host_bits(out2["k_out"]), want_k)
+
+
+def _check_sampled_heads(p, out, samples, band):
+    """Full-size runs: budgets bit-exact for every head; scores, kept sets and compacted rows of
+    the sampled (sequence, layer, kv head) triples against the oracle; for every head the
+    properties that hold at any size (count = budget, ascending, sink and window kept, rows
+    bitwise the source's)."""
+    wl, a = p.wl, p.alloc
+    cu, w, G = wl.cu_seqlens, wl.window, wl.n_q_heads // wl.n_kv_heads
+    NL, H = wl.n_layers, wl.n_kv_heads
+    budgets_ref = np.concatenate([O.allocate(a["curves"][s], a["knots"][s], a["b_min"][s], a["b_max"][s],
+                                             int(a["B"][s]))[0] for s in range(wl.n_seqs)])
+    offsets_ref = O.offsets_of(budgets_ref)
+    assert np.array_equal(out["budgets"].cpu().numpy(), budgets_ref)
+    assert np.array_equal(out["offsets"].cpu().numpy(), offsets_ref)
+    assert int(out["status"].abs().sum()) == 0
+    kept, ko, vo = out["kept_idx"].cpu().numpy(), host_bits(out["k_out"]), host_bits(out["v_out"])
+    pooled = out["pooled"].cpu().numpy()
+    for s in range(wl.n_seqs):
+        L = int(cu[s + 1] - cu[s])
+        forced = np.concatenate([np.arange(wl.n_sink), np.arange(L - w, L)])
+        for l in range(NL):
+            for c in range(H):
+                hi = (s * NL + l) * H + c
+                lo, hi_end = int(offsets_ref[hi]), int(offsets_ref[hi + 1])
+                idx = kept[lo:hi_end]
+                assert idx.size == budgets_ref[hi] and np.all(np.diff(idx) > 0) and idx[0] >= 0 and idx[-1] < L
+                assert np.isin(forced, idx).all(), "sink / window positions must be kept"
+                assert np.array_equal(ko[lo:hi_end], p.data["k"][l, c, cu[s]:cu[s + 1]][idx])
+                assert np.array_equal(vo[lo:hi_end], p.data["v"][l, c, cu[s]:cu[s + 1]][idx])
+    n_band = 0
+    for s, l, c in samples:
+        print("oracle sample seq", s, "layer", l, "kv head", c, flush=True)
+        q = O.decode(p.data["q_win"][l, c * G:(c + 1) * G, s * w:(s + 1) * w, :])
+        kk = O.decode(p.data["k"][l, c:c + 1, cu[s]:cu[s + 1], :])
+        S = O.score(q, kk, 1, w, wl.pool_kernel, wl.n_sink)[0]
+        assert_scores_close(pooled[l, c, cu[s]:cu[s + 1]], S)
+        hi = (s * NL + l) * H + c
+        lo, hi_end = int(offsets_ref[hi]), int(offsets_ref[hi + 1])
+        n_band += check_band(kept[lo:hi_end], O.select(S, int(budgets_ref[hi])), S, band)
+    return n_band
+
+
+def test_evict_full_size_long_context_layer():
+    """One layer of the long-context configuration (L = 131072, w = 64, 5 %): two row groups per
+    workgroup, 2048-key chunks, 128 selection slices per head."""
+    print("case long_128k, one layer", flush=True)
+    wl = dataclasses.replace(synth.workload("long_128k"), n_layers=1, name="long_128k_layer")
+    p = Problem(wl)
+    out = p.evict()
+    n_band = _check_sampled_heads(p, out, [(0, 0, 1), (0, 0, 6)], band=1e-3)
+    print("long_128k band-only index differences in the sampled heads:", n_band)
+
+
+@pytest.mark.timeout(400)
+def test_evict_full_size_ragged_batch():
+    """The ragged batch (16 packed sequences, 4096..65536 tokens, per-sequence allocation)."""
+    print("case batched", flush=True)
+    wl = synth.workload("batched")
+    p = Problem(wl)
+    out = p.evict()
+    order = np.argsort(wl.seq_lens)
+    samples = [(int(order[0]), 0, 0), (int(order[1]), 0, 5), (int(order[-1]), 0, 3)]
+    n_band = _check_sampled_heads(p, out, samples, band=1e-3)
+    print("batched band-only index differences in the sampled heads:", n_band)
+
+
+@pytest.mark.timeout(400)
+def test_evict_full_size_four_layers_global_budget():
+    """Four layers of the full-prefill configuration at L = 32768: one global allocation over
+    32 layer-heads ("mixed" curve families, some heads all-or-nothing), layer-major launches."""
+    print("case 8b_full_20, four layers", flush=True)
+    wl = dataclasses.replace(synth.workload("8b_full_20"), n_layers=4, name="8b_full_20_4layers")
+    p = Problem(wl)
+    out = p.evict()
+    n_band = _check_sampled_heads(p, out, [(0, 0, 2), (0, 3, 7), (0, 2, 4)], band=1e-3)
+    print("8b_full_20 (4 layers) band-only index differences in the sampled heads:", n_band)
