@@ -9,7 +9,9 @@ A plain, slow, fp64 statement of what the path computes, written from the paper:
              greedy until B_total is spent (Eq. 8's equality constraint);
   select   - Sec. 3.2 symbol table, M^pi(k): top-k by the metric, descending, with the
              fixed deterministic tie rule App. A.1 assumes (lowest index first);
-  compact  - Sec. 3.2 / Eq. 3: the retained index set I_{l,h} as a dense per-head cache.
+  compact  - Sec. 3.2 / Eq. 3: the retained index set I_{l,h} as a dense per-head cache;
+  profile  - Sec. 4.3, Eq. 11 and "Online Execution": the static table of local ratios over a
+             grid of global ratios, and the look-up that turns a target ratio into budgets.
 
 Only tests, the smoke check and the benchmark's cpu_baseline leg may import this
 module.  It shares no code with the HIP path and never calls it.
@@ -224,6 +226,55 @@ def allocate(curves: np.ndarray, knots: np.ndarray, b_min: np.ndarray, b_max: np
 def offsets_of(budgets: np.ndarray) -> np.ndarray:
     """Row offset of every head in the packed outputs: exclusive prefix sum, int64 [NH+1]."""
     return np.concatenate([[0], np.cumsum(budgets.astype(np.int64))]).astype(np.int64)
+
+
+# ----------------------------------------------------------------------------
+# offline profile and online look-up (Sec. 4.3, Eq. 11; "Online Execution" steps 1-2)
+# ----------------------------------------------------------------------------
+
+def profile_build(curves: np.ndarray, knots: np.ndarray, b_min: np.ndarray, b_max: np.ndarray,
+                  L: int, rho: Sequence[float]) -> np.ndarray:
+    """Static profile Phi[n_rho, NH] (float32): for every calibration query m and every global
+    compression ratio rho on the grid, solve the relaxed allocation (Eq. 10) with
+    B = floor((1 - rho) * L * NH) and take the local ratios r* = 1 - b / L; Phi is their mean
+    over the queries (Eq. 11).
+
+    curves, knots [M, NH, Gp]; b_min, b_max [M, NH].  Reading: a ratio whose budget is not
+    feasible (below the minimum retention) takes allocate()'s documented result, b = b_min.
+    The mean is the fp64 sum over m in order, divided by M, rounded to float32.
+    """
+    M, NH = curves.shape[0], curves.shape[1]
+    phi = np.zeros((len(rho), NH), dtype=np.float64)
+    for ri, r in enumerate(rho):
+        B = int(math.floor((1.0 - float(r)) * float(L) * float(NH)))
+        acc = np.zeros(NH, dtype=np.float64)
+        for m in range(M):
+            b, _ = allocate(curves[m], knots[m], b_min[m], b_max[m], B)
+            acc = acc + (1.0 - b.astype(np.float64) / float(L))
+        phi[ri] = acc / float(M)
+    return phi.astype(np.float32)
+
+
+def budgets_from_profile(phi: np.ndarray, rho: Sequence[float], sigma: float, L: int,
+                         b_min: np.ndarray, b_max: np.ndarray) -> np.ndarray:
+    """Online steps 1-2: look the local ratios up at the target global ratio sigma (linear
+    between the two neighbouring grid ratios, end values outside the grid) and turn them into
+    integer budgets b = floor((1 - r) * L), kept inside [b_min, b_max].  fp64 throughout:
+    t = (sigma - rho_i) / (rho_{i+1} - rho_i), r = phi_i + t * (phi_{i+1} - phi_i)."""
+    rho = [float(x) for x in rho]
+    n = len(rho)
+    if n == 1 or sigma <= rho[0]:
+        r = phi[0].astype(np.float64)
+    elif sigma >= rho[-1]:
+        r = phi[-1].astype(np.float64)
+    else:
+        i = max(j for j in range(n - 1) if rho[j] <= sigma)
+        t = (float(sigma) - rho[i]) / (rho[i + 1] - rho[i])
+        lo, hi = phi[i].astype(np.float64), phi[i + 1].astype(np.float64)
+        r = lo + t * (hi - lo)
+    b = np.floor((1.0 - r) * float(L)).astype(np.int64)
+    b = np.minimum(np.maximum(b, b_min.astype(np.int64)), b_max.astype(np.int64))
+    return b.astype(np.int32)
 
 
 # ----------------------------------------------------------------------------

@@ -98,7 +98,7 @@ template <bool POOL>
 __global__ __launch_bounds__(1024) void sel_hist_kernel(SelGeom sg, SeqTab tab, AllocIO aio,
                                                         int n_alloc_blocks, const float* src_scores,
                                                         float* pooled_out, const float2* range,
-                                                        unsigned* hist_parts, uint2* head_dig,
+                                                        unsigned* hist_parts,
                                                         unsigned long long* by_bin, int32_t* status) {
   __shared__ __align__(16) char scratch[49152];
   unsigned* lh = reinterpret_cast<unsigned*>(scratch);                      // kHistBins counters
@@ -190,7 +190,6 @@ __global__ __launch_bounds__(1024) void sel_hist_kernel(SelGeom sg, SeqTab tab, 
   lh[2046 - 2 * t] = s_hi;
   __syncthreads();
   if (j < L) by_bin[base + j0 + lh[bin] + rank] = ((unsigned long long)key << 32) | (unsigned)j;
-  if (t == 0 && sl == 0) head_dig[hi] = make_uint2(lo, shift);
 }
 
 // Exact threshold T among the n_c candidates of the list (the want-th largest, ties included)
@@ -540,7 +539,6 @@ int launch_select_compact(const HostCfg& hc, const WsLayout& lay, const AllocIO*
              pool ? lay.max_chunks * 4 : lay.max_slices};
   unsigned* hist = reinterpret_cast<unsigned*>(ws + lay.hist);
   float2* range = reinterpret_cast<float2*>(ws + lay.range);
-  uint2* head_dig = reinterpret_cast<uint2*>(ws + lay.head_dig);
   uint4* state = reinterpret_cast<uint4*>(ws + lay.sel_state);
   uint2* slice_cnt = reinterpret_cast<uint2*>(ws + lay.slice_cnt);
   unsigned long long* by_bin = reinterpret_cast<unsigned long long*>(ws + lay.by_bin);
@@ -556,11 +554,11 @@ int launch_select_compact(const HostCfg& hc, const WsLayout& lay, const AllocIO*
   stage_mark(kStHist, st);
   if (pool) {
     hipLaunchKernelGGL(sel_hist_kernel<true>, gridH, dim3(1024), 0, st, sg, tabH, io, n_alloc, scores_in,
-                       pooled_out, (const float2*)range, hist, head_dig, by_bin, status);
+                       pooled_out, (const float2*)range, hist, by_bin, status);
   } else {
     hipLaunchKernelGGL(sel_range_kernel, gridR, dim3(1024), 0, st, sg, tabH, scores_in, range);
     hipLaunchKernelGGL(sel_hist_kernel<false>, gridH, dim3(1024), 0, st, sg, tabH, io, n_alloc, scores_in,
-                       (float*)nullptr, (const float2*)range, hist, head_dig, by_bin, status);
+                       (float*)nullptr, (const float2*)range, hist, by_bin, status);
   }
   const float* sel_scores = pool ? pooled_out : scores_in;
   stage_mark(kStTail, st);

@@ -249,6 +249,47 @@ def test_offsets_are_prefix_sums():
     assert O.offsets_of(np.array([3, 0, 5], np.int32)).tolist() == [0, 3, 3, 8]
 
 
+# --- profile and look-up --------------------------------------------------------------------
+
+def test_handworked_profile_and_lookup():
+    g, U, knots = _curves()
+    zero, four = np.zeros((1, 2), np.int32), np.full((1, 2), 4, np.int32)
+    rho = [0.0, 0.25, 0.5, 0.75, 1.0]
+    phi = O.profile_build(U[None], knots[None], zero, four, 4, rho)
+    assert phi.dtype == np.float32 and phi.shape == (5, 2)
+    assert phi[:, 0].tolist() == [float(Fraction(t)) for t in g["phi_h0"]]
+    assert phi[:, 1].tolist() == [float(Fraction(t)) for t in g["phi_h1"]]
+    for key, sigma in (("lookup_3_8", 0.375), ("lookup_5_8", 0.625)):
+        b = O.budgets_from_profile(phi, rho, sigma, 4, zero[0], four[0])
+        assert b.tolist() == [int(t) for t in g[key][0].split(",")]
+    # on a grid ratio the look-up returns that row's budgets; outside the grid, the end rows
+    assert O.budgets_from_profile(phi, rho, 0.5, 4, zero[0], four[0]).tolist() == [3, 1]
+    assert O.budgets_from_profile(phi, rho, -1.0, 4, zero[0], four[0]).tolist() == [4, 4]
+    assert O.budgets_from_profile(phi, rho, 2.0, 4, zero[0], four[0]).tolist() == [0, 0]
+    # bounds clip the looked-up budgets
+    assert O.budgets_from_profile(phi, rho, 0.625, 4, np.array([3, 0], np.int32), np.array([4, 0], np.int32)).tolist() == [3, 0]
+    # two calibration queries: the mean of their local ratios (Eq. 11)
+    U2 = np.stack([U, U[::-1]])
+    phi2 = O.profile_build(U2, np.stack([knots, knots]), np.zeros((2, 2), np.int32), np.full((2, 2), 4, np.int32), 4, rho)
+    assert phi2[2].tolist() == [float(Fraction(t)) for t in g["phi2_rho_1_2"]]
+
+
+def test_profile_rows_reproduce_the_allocation_on_the_grid():
+    """For one query, looking the profile up AT a grid ratio gives back that ratio's budgets
+    (1 - b/L is exact in fp32 for these sizes), and the budgets sum to floor((1-rho) L NH)."""
+    NH, Gp, L = 5, 9, 64
+    U, knots, b_min, b_max = _random_problem(900, NH, Gp, L)
+    b_min[:] = 0
+    b_max[:] = L
+    rho = [i / 8 for i in range(9)]
+    phi = O.profile_build(U[None], knots[None], b_min[None], b_max[None], L, rho)
+    for i, r in enumerate(rho):
+        b = O.budgets_from_profile(phi, rho, r, L, b_min, b_max)
+        want, st = O.allocate(U, knots, b_min, b_max, int((1 - r) * L * NH))
+        assert st == 0 and b.tolist() == want.tolist()
+    assert np.all(np.diff(phi, axis=0) >= 0)        # compressing more never keeps more in a head
+
+
 # --- top-k and compaction -----------------------------------------------------------------
 
 @pytest.mark.parametrize("seed", range(5))

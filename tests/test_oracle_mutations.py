@@ -15,7 +15,8 @@ from tests import test_oracle_allocate as TA
 from tests import test_oracle_score as TS
 
 PUBLIC = ["window_attention_sum", "window_lse", "max_pool_1d", "score", "concave_hull", "marginal_gains",
-          "_gain_of_unit", "_slope", "allocate", "select", "compact", "offsets_of"]
+          "_gain_of_unit", "_slope", "allocate", "select", "compact", "offsets_of", "profile_build",
+          "budgets_from_profile"]
 
 MUTANTS = {
     # name: (snippet, replacement, pin that must fail)
@@ -45,6 +46,17 @@ MUTANTS = {
                           lambda: TS.test_lse_variant_equals_recomputed_normaliser()),
     "lse_not_causal": ("row = s[i, :L - w + i + 1]", "row = s[i, :]",
                        lambda: TS.test_handworked_lse_variant()),
+    "profile_keeps_instead_of_evicts": ("acc = acc + (1.0 - b.astype(np.float64) / float(L))",
+                                        "acc = acc + (b.astype(np.float64) / float(L))",
+                                        lambda: TA.test_handworked_profile_and_lookup()),
+    "profile_budget_from_rho_not_one_minus_rho": ("B = int(math.floor((1.0 - float(r)) * float(L) * float(NH)))",
+                                                  "B = int(math.floor(float(r) * float(L) * float(NH)))",
+                                                  lambda: TA.test_handworked_profile_and_lookup()),
+    "lookup_rounds_instead_of_floor": ("b = np.floor((1.0 - r) * float(L)).astype(np.int64)",
+                                       "b = np.rint((1.0 - r) * float(L)).astype(np.int64)",
+                                       lambda: TA.test_handworked_profile_and_lookup()),
+    "lookup_no_interpolation": ("r = lo + t * (hi - lo)", "r = lo",
+                                lambda: TA.test_handworked_profile_and_lookup()),
     "sink_not_forced": ("s[:, :min(n_sink, L)] = np.inf", "pass",
                         lambda: TS.test_brute_force_definition()),
     "hull_keeps_collinear": ("if steepness_in > steepness_out:", "if steepness_in >= steepness_out:",
