@@ -157,6 +157,44 @@ int lukv_evict_lse(const lukv_config* cfg, const void* q_win, const void* k, con
                    void* k_out, void* v_out, float* pooled, int32_t* status,
                    void* ws, int64_t ws_bytes, void* stream);
 
+/* The static profile and the online look-up (Sec. 4.3: Eq. 11 and "Online Execution" steps 1-2).
+ *
+ * lukv_profile_build: for every calibration query m (its own utility curves, as in
+ * lukv_allocate) and every global compression ratio rho[r] of the grid, the relaxed allocation
+ * with B = floor((1 - rho[r]) * L * n_heads) gives local ratios 1 - b/L; phi[r][h] is their
+ * mean over the queries (fp64 sum in query order, divided by n_queries, rounded to float).  A
+ * ratio whose B is infeasible takes lukv_allocate's result for that case (budgets = b_min).
+ *   curves, knots device [n_queries][n_heads][n_grid]; b_min, b_max device [n_queries][n_heads]
+ *   rho HOST double [n_rho], strictly increasing;  phi device float32 [n_rho][n_heads]
+ *   ws: lukv_profile_workspace_bytes(n_queries, n_heads, n_grid) bytes.
+ * Limits as lukv_allocate (n_queries <= LUKV_MAX_SEQS), 1 <= n_rho, 1 <= L.
+ *
+ * lukv_budgets_from_profile: local ratios at sigma_target, linear between the two neighbouring
+ * grid ratios (the end rows outside the grid): t = (sigma - rho_i) / (rho_{i+1} - rho_i),
+ * r = phi_i + t * (phi_{i+1} - phi_i) in fp64; budgets[h] = floor((1 - r) * L) kept inside
+ * [b_min[h], b_max[h]]; offsets = exclusive prefix sum.  Needs no workspace.
+ *   phi device [n_rho][n_heads]; b_min, b_max device int32 [n_heads]
+ *   budgets device int32 [n_heads]; offsets device int64 [n_heads + 1]. */
+int lukv_profile_workspace_bytes(int32_t n_queries, int32_t n_heads, int32_t n_grid, int64_t* bytes);
+int lukv_profile_build(int32_t n_queries, int32_t n_heads, int32_t n_grid, const float* curves,
+                       const int32_t* knots, const int32_t* b_min, const int32_t* b_max, int32_t L,
+                       int32_t n_rho, const double* rho, float* phi, void* ws, int64_t ws_bytes,
+                       void* stream);
+int lukv_budgets_from_profile(int32_t n_heads, int32_t n_rho, const double* rho, const float* phi,
+                              double sigma_target, int32_t L, const int32_t* b_min,
+                              const int32_t* b_max, int32_t* budgets, int64_t* offsets, void* stream);
+
+/* The online mode's eviction (Sec. 4.3 "Online Execution" step 3): budgets are given (for
+ * example by lukv_budgets_from_profile), so score -> select -> compact run without the
+ * allocation.  Heads ordered as everywhere (one sequence's heads are (layer, kv_head)).
+ *   lse may be NULL (the statistics pass then runs) or as in lukv_score_lse
+ *   budgets device int32 [n_heads_total], offsets device int64 [n_heads_total + 1] (inputs)
+ *   out_rows, kept_idx, k_out, v_out, status [1] as in lukv_select_compact; pooled may be NULL. */
+int lukv_evict_budgets(const lukv_config* cfg, const void* q_win, const void* k, const void* v,
+                       const float* lse, const int32_t* budgets, const int64_t* offsets,
+                       int64_t out_rows, int32_t* kept_idx, void* k_out, void* v_out, float* pooled,
+                       int32_t* status, void* ws, int64_t ws_bytes, void* stream);
+
 /* Instrumentation for benchmarks (process-wide, not thread-safe; for callers that time the path,
  * not part of the method).  While n_events > 0, every call records events[i] (hipEvent_t, created
  * by the caller, passed as void*) on its stream immediately before stage i, and lukv_evict records

@@ -283,6 +283,97 @@ int lukv_evict_lse(const lukv_config* cfg, const void* q_win, const void* k, con
                     offsets, kept_idx, k_out, v_out, pooled, status, ws, ws_bytes, stream);
 }
 
+// profile scratch after the allocation scratch: budgets, offsets, status of the queries
+struct ProfileWs { WsLayout lay; int64_t budgets, offsets, status, total; };
+static ProfileWs profile_layout(int32_t n_queries, int32_t n_heads, int32_t n_grid) {
+  ProfileWs p;
+  p.lay = alloc_only_layout(n_queries, n_heads, n_grid);
+  int64_t off = p.lay.total;
+  auto take = [&](int64_t bytes) { const int64_t o = off; off = align_up(off + bytes, 256); return o; };
+  p.budgets = take((int64_t)n_queries * n_heads * 4);
+  p.offsets = take(((int64_t)n_queries * n_heads + 1) * 8);
+  p.status = take((int64_t)n_queries * 4);
+  p.total = off;
+  return p;
+}
+
+static bool profile_dims_ok(int32_t n_queries, int32_t n_heads, int32_t n_grid) {
+  return n_queries >= 1 && n_queries <= LUKV_MAX_SEQS && n_heads >= 1 && n_grid >= 2 && n_grid <= kMaxGrid &&
+         (int64_t)n_queries * n_heads <= (1 << 24);
+}
+
+int lukv_profile_workspace_bytes(int32_t n_queries, int32_t n_heads, int32_t n_grid, int64_t* bytes) {
+  if (!bytes || !profile_dims_ok(n_queries, n_heads, n_grid)) return LUKV_EINVAL;
+  *bytes = profile_layout(n_queries, n_heads, n_grid).total;
+  return LUKV_OK;
+}
+
+int lukv_profile_build(int32_t n_queries, int32_t n_heads, int32_t n_grid, const float* curves,
+                       const int32_t* knots, const int32_t* b_min, const int32_t* b_max, int32_t L,
+                       int32_t n_rho, const double* rho, float* phi, void* ws, int64_t ws_bytes,
+                       void* stream) {
+  if (!profile_dims_ok(n_queries, n_heads, n_grid) || L < 1 || n_rho < 1) return LUKV_EINVAL;
+  if (!curves || !knots || !b_min || !b_max || !rho || !phi) return LUKV_EINVAL;
+  for (int r = 0; r < n_rho; ++r)
+    if (!(rho[r] == rho[r]) || (r > 0 && !(rho[r] > rho[r - 1]))) return LUKV_EINVAL;
+  const ProfileWs pw = profile_layout(n_queries, n_heads, n_grid);
+  if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u) || ws_bytes < pw.total) return LUKV_EWORKSPACE;
+  char* w = (char*)ws;
+  const AllocIO io = make_alloc_io(n_queries, n_heads, n_grid, curves, knots, b_min, b_max, nullptr,
+                                   reinterpret_cast<int32_t*>(w + pw.budgets),
+                                   reinterpret_cast<int64_t*>(w + pw.offsets),
+                                   reinterpret_cast<int32_t*>(w + pw.status), pw.lay, w);
+  return launch_profile_build(io, L, n_rho, rho, phi, static_cast<hipStream_t>(stream));
+}
+
+int lukv_budgets_from_profile(int32_t n_heads, int32_t n_rho, const double* rho, const float* phi,
+                              double sigma_target, int32_t L, const int32_t* b_min,
+                              const int32_t* b_max, int32_t* budgets, int64_t* offsets, void* stream) {
+  if (n_heads < 1 || n_rho < 1 || L < 1 || !rho || !phi || !b_min || !b_max || !budgets || !offsets)
+    return LUKV_EINVAL;
+  if (!(sigma_target == sigma_target)) return LUKV_EINVAL;
+  for (int r = 1; r < n_rho; ++r)
+    if (!(rho[r] > rho[r - 1])) return LUKV_EINVAL;
+  int lo = 0, hi = 0;
+  double t = 0.0;
+  if (n_rho == 1 || sigma_target <= rho[0]) {
+    lo = hi = 0;
+  } else if (sigma_target >= rho[n_rho - 1]) {
+    lo = hi = n_rho - 1;
+  } else {
+    for (int r = 0; r + 1 < n_rho; ++r)
+      if (rho[r] <= sigma_target) lo = r;
+    hi = lo + 1;
+    t = (sigma_target - rho[lo]) / (rho[hi] - rho[lo]);
+  }
+  return launch_profile_lookup(phi + (int64_t)lo * n_heads, phi + (int64_t)hi * n_heads, t, n_heads, L, b_min,
+                               b_max, budgets, offsets, static_cast<hipStream_t>(stream));
+}
+
+int lukv_evict_budgets(const lukv_config* cfg, const void* q_win, const void* k, const void* v,
+                       const float* lse, const int32_t* budgets, const int64_t* offsets,
+                       int64_t out_rows, int32_t* kept_idx, void* k_out, void* v_out, float* pooled,
+                       int32_t* status, void* ws, int64_t ws_bytes, void* stream) {
+  HostCfg hc;
+  int rc = validate_config(cfg, &hc);
+  if (rc) return rc;
+  if (!q_win || !k || !v || !budgets || !offsets || !kept_idx || !k_out || !v_out || !status || out_rows < 0)
+    return LUKV_EINVAL;
+  if (!aligned16(q_win) || !aligned16(k) || !aligned16(v) || !aligned16(k_out) || !aligned16(v_out))
+    return LUKV_EINVAL;
+  const WsLayout lay = make_layout(hc, 0, false);
+  if ((rc = check_ws(lay, ws, ws_bytes))) return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  char* w = (char*)ws;
+  float* scores = pooled ? pooled : reinterpret_cast<float*>(w + lay.pooled);
+  if ((rc = launch_score_raw(hc, lay, q_win, k, lse, nullptr, w, st))) return rc;
+  rc = launch_select_compact(hc, lay, nullptr, reinterpret_cast<const float*>(w + lay.raw), true, scores, budgets,
+                             const_cast<int64_t*>(offsets), false, k, v, kept_idx, k_out, v_out, out_rows,
+                             status, w, st);
+  stage_mark(kStEnd, st);
+  return rc;
+}
+
 int lukv_set_stage_events(void* const* events, int32_t n_events) {
   if (n_events < 0 || (n_events > 0 && !events)) return LUKV_EINVAL;
   g_stage_events = n_events ? events : nullptr;

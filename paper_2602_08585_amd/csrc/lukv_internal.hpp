@@ -91,6 +91,13 @@ AllocIO make_alloc_io(int32_t n_problems, int32_t n_heads, int32_t n_grid, const
                       const int64_t* B_total, int32_t* budgets, int64_t* offsets, int32_t* status,
                       const WsLayout& lay, char* ws);
 int launch_allocate(const AllocIO& io, hipStream_t st);
+// static profile (Eq. 11): io0 describes the calibration queries as allocation problems whose
+// budgets / status arrays are scratch; rho is a host array
+int launch_profile_build(const AllocIO& io0, int32_t L, int32_t n_rho, const double* rho, float* phi,
+                         hipStream_t st);
+int launch_profile_lookup(const float* row_lo, const float* row_hi, double t, int32_t n_heads, int32_t L,
+                          const int32_t* b_min, const int32_t* b_max, int32_t* budgets, int64_t* offsets,
+                          hipStream_t st);
 
 // Optional instrumentation (lukv_set_stage_events): record the caller's event for a stage.
 enum Stage { kStAllocate = 0, kStStats, kStAccum, kStPool, kStHist, kStTail, kStEmit, kStEnd,

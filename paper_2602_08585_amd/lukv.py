@@ -33,7 +33,8 @@ LUKV_ST_CLAMPED = 2
 
 EXPORTS = ("lukv_workspace_bytes", "lukv_allocate_workspace_bytes", "lukv_score", "lukv_allocate",
            "lukv_select_compact", "lukv_evict", "lukv_score_lse", "lukv_evict_lse",
-           "lukv_set_stage_events", "lukv_stage_name", "lukv_strerror")
+           "lukv_profile_workspace_bytes", "lukv_profile_build", "lukv_budgets_from_profile",
+           "lukv_evict_budgets", "lukv_set_stage_events", "lukv_stage_name", "lukv_strerror")
 LUKV_STAGE_END = 7
 LUKV_NUM_STAGE_EVENTS = 8
 
@@ -80,6 +81,11 @@ def load_library() -> ctypes.CDLL:
     lib.lukv_score_lse.argtypes = [CP, P, P, P, P, P, I64, P]
     lib.lukv_evict_lse.argtypes = [CP, P, P, P, P, I32, P, P, P, P, ctypes.POINTER(I64),
                                    P, P, P, P, P, P, P, P, I64, P]
+    F64P = ctypes.POINTER(ctypes.c_double)
+    lib.lukv_profile_workspace_bytes.argtypes = [I32, I32, I32, ctypes.POINTER(I64)]
+    lib.lukv_profile_build.argtypes = [I32, I32, I32, P, P, P, P, I32, I32, F64P, P, P, I64, P]
+    lib.lukv_budgets_from_profile.argtypes = [I32, I32, F64P, P, ctypes.c_double, I32, P, P, P, P, P]
+    lib.lukv_evict_budgets.argtypes = [CP, P, P, P, P, P, P, I64, P, P, P, P, P, P, I64, P]
     lib.lukv_set_stage_events.argtypes = [ctypes.POINTER(ctypes.c_void_p), I32]
     lib.lukv_stage_name.argtypes = [I32]
     lib.lukv_stage_name.restype = ctypes.c_char_p
@@ -248,6 +254,44 @@ def lukv_evict_lse(cfg: Config, q_win, k, v, lse, n_grid: int, curves, knots, b_
                                          _ptr(kept_idx), _ptr(k_out), _ptr(v_out), _ptr(pooled),
                                          _ptr(status), _ptr(ws), ws.numel(), _stream(stream)),
            "lukv_evict_lse")
+
+
+def _host_f64(x: Sequence[float]):
+    arr = np.ascontiguousarray(np.asarray(x, dtype=np.float64))
+    return arr, arr.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+
+
+def lukv_profile_workspace_bytes(n_queries: int, n_heads: int, n_grid: int) -> int:
+    out = ctypes.c_int64(0)
+    _check(load_library().lukv_profile_workspace_bytes(n_queries, n_heads, n_grid, ctypes.byref(out)),
+           "lukv_profile_workspace_bytes")
+    return out.value
+
+
+def lukv_profile_build(n_queries: int, n_heads: int, n_grid: int, curves, knots, b_min, b_max, L: int,
+                       rho: Sequence[float], phi, ws, stream=None) -> None:
+    keep, rp = _host_f64(rho)
+    _check(load_library().lukv_profile_build(n_queries, n_heads, n_grid, _ptr(curves), _ptr(knots),
+                                             _ptr(b_min), _ptr(b_max), int(L), len(keep), rp, _ptr(phi),
+                                             _ptr(ws), ws.numel(), _stream(stream)), "lukv_profile_build")
+
+
+def lukv_budgets_from_profile(n_heads: int, rho: Sequence[float], phi, sigma_target: float, L: int,
+                              b_min, b_max, budgets, offsets, stream=None) -> None:
+    keep, rp = _host_f64(rho)
+    _check(load_library().lukv_budgets_from_profile(n_heads, len(keep), rp, _ptr(phi), float(sigma_target),
+                                                    int(L), _ptr(b_min), _ptr(b_max), _ptr(budgets),
+                                                    _ptr(offsets), _stream(stream)),
+           "lukv_budgets_from_profile")
+
+
+def lukv_evict_budgets(cfg: Config, q_win, k, v, lse, budgets, offsets, out_rows: int, kept_idx, k_out,
+                       v_out, pooled, status, ws, stream=None) -> None:
+    _check(load_library().lukv_evict_budgets(ctypes.byref(cfg.to_c()), _ptr(q_win), _ptr(k), _ptr(v),
+                                             _ptr(lse), _ptr(budgets), _ptr(offsets), int(out_rows),
+                                             _ptr(kept_idx), _ptr(k_out), _ptr(v_out), _ptr(pooled),
+                                             _ptr(status), _ptr(ws), ws.numel(), _stream(stream)),
+           "lukv_evict_budgets")
 
 
 def lukv_set_stage_events(events) -> None:

@@ -460,3 +460,89 @@ def test_evict_full_size_four_layers_global_budget():
     out = p.evict()
     n_band = _check_sampled_heads(p, out, [(0, 0, 2), (0, 3, 7), (0, 2, 4)], band=1e-3)
     print("8b_full_20 (4 layers) band-only index differences in the sampled heads:", n_band)
+
+
+def _calibration_curves(wl, n_queries):
+    """n_queries sets of utility curves of the workload's shape (one per calibration query)."""
+    sets = [synth.make_allocation_inputs(dataclasses.replace(wl, seed=wl.seed + 17 * m)) for m in range(n_queries)]
+    return {k: np.concatenate([x[k] for x in sets]) for k in ("curves", "knots", "b_min", "b_max")}
+
+
+@pytest.mark.parametrize("name,n_queries,rho", [
+    ("tiny", 3, [i / 16 for i in range(17)]),
+    ("8b_32k", 5, [i / 16 for i in range(17)]),
+    # 256 layer-heads: the oracle hands units out one by one, so only strong compression here
+    ("8b_full_20", 2, [0.9, 0.95, 0.98])])
+def test_profile_build_and_lookup_parity(name, n_queries, rho):
+    """Static profile over a ratio grid (Eq. 11) and the online look-up: bit-exact."""
+    print("case", name, flush=True)
+    wl = synth.workload(name)
+    c = _calibration_curves(wl, n_queries)
+    NH, Gp, L = wl.heads_per_problem, wl.n_grid, wl.seq_lens[0]
+    want = O.profile_build(c["curves"], c["knots"], c["b_min"], c["b_max"], L, rho)
+    phi = torch.full((len(rho), NH), float("nan"), dtype=torch.float32, device="cuda")
+    ws = lukv.alloc_workspace(lukv.lukv_profile_workspace_bytes(n_queries, NH, Gp))
+    lukv.lukv_profile_build(n_queries, NH, Gp, dev(c["curves"]), dev(c["knots"]), dev(c["b_min"]),
+                            dev(c["b_max"]), L, rho, phi, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(phi.cpu().numpy(), want)
+    budgets = torch.zeros(NH, dtype=torch.int32, device="cuda")
+    offsets = torch.zeros(NH + 1, dtype=torch.int64, device="cuda")
+    b_min, b_max = c["b_min"][0], c["b_max"][0]
+    for sigma in (0.8, 0.8125, 0.33, 0.999, -0.5, 1.5, 0.5 + 1e-9, 0.93, 0.97):
+        lukv.lukv_budgets_from_profile(NH, rho, phi, sigma, L, dev(b_min), dev(b_max), budgets, offsets)
+        torch.cuda.synchronize()
+        ref = O.budgets_from_profile(want, rho, sigma, L, b_min, b_max)
+        assert np.array_equal(budgets.cpu().numpy(), ref), sigma
+        assert np.array_equal(offsets.cpu().numpy(), O.offsets_of(ref))
+
+
+@pytest.mark.parametrize("use_lse", [False, True])
+def test_online_mode_profile_lookup_then_evict(use_lse):
+    """The paper's online mode end to end: look budgets up in a static profile, then
+    score -> top-k -> compact with those budgets (no allocation in the call)."""
+    print("case online mode, lse =", use_lse, flush=True)
+    p = _problem("bf16_ragged")
+    wl = p.wl
+    assert wl.n_seqs == 3
+    NH, Gp = wl.heads_per_problem, wl.n_grid
+    rho = [i / 8 for i in range(9)]
+    budgets_all, out_rows = [], 0
+    for s, L in enumerate(wl.seq_lens):
+        # one profile per sequence length here (knots are in tokens); three calibration queries
+        wl_s = dataclasses.replace(wl, seq_lens=[L])
+        c = _calibration_curves(wl_s, 3)
+        phi = O.profile_build(c["curves"], c["knots"], c["b_min"], c["b_max"], L, rho)
+        phi_d = dev(phi)
+        b = torch.zeros(NH, dtype=torch.int32, device="cuda")
+        o = torch.zeros(NH + 1, dtype=torch.int64, device="cuda")
+        lukv.lukv_budgets_from_profile(NH, rho, phi_d, 0.7, L, dev(c["b_min"][0]), dev(c["b_max"][0]), b, o)
+        torch.cuda.synchronize()
+        ref_b = O.budgets_from_profile(phi, rho, 0.7, L, c["b_min"][0], c["b_max"][0])
+        assert np.array_equal(b.cpu().numpy(), ref_b)
+        budgets_all.append(ref_b)
+    budgets_h = np.concatenate(budgets_all)
+    offsets_h = O.offsets_of(budgets_h)
+    out = p.new_outputs(rows=int(offsets_h[-1]))
+    lse_h = p.oracle_lse() if use_lse else None
+    lukv.lukv_evict_budgets(p.cfg, p.q, p.k, p.v, dev(lse_h) if use_lse else None, dev(budgets_h), dev(offsets_h),
+                            out["kept_idx"].numel(), out["kept_idx"], out["k_out"], out["v_out"], out["pooled"],
+                            out["status"][:1], p.ws)
+    torch.cuda.synchronize()
+    assert int(out["status"][0]) == 0
+    kept, ko, vo = out["kept_idx"].cpu().numpy(), host_bits(out["k_out"]), host_bits(out["v_out"])
+    pooled = out["pooled"].cpu().numpy()
+    cu, w = wl.cu_seqlens, wl.window
+    for s in range(wl.n_seqs):
+        for l in range(wl.n_layers):
+            q = O.decode(p.data["q_win"][l, :, s * w:(s + 1) * w, :])
+            kk = O.decode(p.data["k"][l, :, cu[s]:cu[s + 1], :])
+            row_lse = None if lse_h is None else lse_h[l, :, s * w:(s + 1) * w]
+            S = O.score(q, kk, wl.n_kv_heads, w, wl.pool_kernel, wl.n_sink, lse=row_lse)
+            assert_scores_close(pooled[l, :, cu[s]:cu[s + 1]], S)
+            for c in range(wl.n_kv_heads):
+                hi = (s * wl.n_layers + l) * wl.n_kv_heads + c
+                a, b = int(offsets_h[hi]), int(offsets_h[hi + 1])
+                check_band(kept[a:b], O.select(S[c], int(budgets_h[hi])), S[c], BAND)
+                assert np.array_equal(ko[a:b], p.data["k"][l, c, cu[s]:cu[s + 1]][kept[a:b]])
+                assert np.array_equal(vo[a:b], p.data["v"][l, c, cu[s]:cu[s + 1]][kept[a:b]])
