@@ -43,6 +43,10 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=320)
     ap.add_argument("--warmup", type=int, default=32)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--layers", type=int, default=1,
+                    help="1 (default): the headline workload, one 8B-shaped layer at 32k.  N > 1: "
+                         "N layers of the full-prefill configuration in ONE call (one global "
+                         "allocation over 8N layer-heads); an extra figure, no CPU baseline")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a plain elementwise pass over 256 MiB (read 256 MiB, write 256 MiB) "
                          "four times before the warm-up: the known-size kernel that scales the "
@@ -60,7 +64,14 @@ def main() -> int:
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     lukv.load_library()
-    wl = synth.workload("8b_32k")
+    NL = args.layers
+    if NL == 1:
+        wl = synth.workload("8b_32k")
+    else:
+        import dataclasses
+        wl = dataclasses.replace(synth.workload("8b_full_20"), n_layers=NL, name="8b_full_20_%dlayers" % NL)
+        args.no_cpu_baseline = True
+    n_sets = max(1, N_SETS // NL)
     L, d, Hkv, Hq, w = wl.seq_lens[0], wl.head_dim, wl.n_kv_heads, wl.n_q_heads, wl.window
 
     # ---- inputs: N_SETS distinct layers' worth of Q/K/V, one allocation problem ------------
@@ -69,9 +80,9 @@ def main() -> int:
         return (t.view(torch.bfloat16) if x.dtype == np.uint16 else t).cuda()
 
     sets, host_sets = [], []
-    for i in range(N_SETS):
-        data = synth.make_qkv(wl, layers=[i])
-        if i < N_CPU_SETS:
+    for i in range(n_sets):
+        data = synth.make_qkv(wl, layers=list(range(i * NL, (i + 1) * NL)))
+        if i < N_CPU_SETS and not args.no_cpu_baseline:
             host_sets.append(data)
         sets.append((up(data["q_win"]), up(data["k"]), up(data["v"])))
     alloc = synth.make_allocation_inputs(wl)
@@ -90,7 +101,7 @@ def main() -> int:
     status = torch.zeros(wl.n_seqs + 1, dtype=torch.int32, device="cuda")
 
     def step(i):
-        q, k, v = sets[i % N_SETS]
+        q, k, v = sets[i % n_sets]
         lukv.lukv_evict(cfg, q, k, v, wl.n_grid, curves, knots, b_min, b_max, B, budgets, offsets,
                         kept, k_out, v_out, None, status, ws)
 
@@ -98,17 +109,20 @@ def main() -> int:
     # attention kernel leaves behind), prepared with torch outside every timed region
     def window_lse(q, k):
         G = Hq // Hkv
-        kk = k[0].float().repeat_interleave(G, dim=0)                      # [Hq, L, d]
-        logits = torch.einsum("hid,hjd->hij", q[0].float(), kk) / (d ** 0.5)
         j = torch.arange(L, device="cuda")[None, None, :]
         i = torch.arange(w, device="cuda")[None, :, None]
-        logits = logits.masked_fill(j > L - w + i, float("-inf"))
-        return torch.logsumexp(logits, dim=2)[None].contiguous()           # [1, Hq, w]
+        rows = []
+        for l in range(NL):
+            kk = k[l].float().repeat_interleave(G, dim=0)                  # [Hq, L, d]
+            logits = torch.einsum("hid,hjd->hij", q[l].float(), kk) / (d ** 0.5)
+            logits = logits.masked_fill(j > L - w + i, float("-inf"))
+            rows.append(torch.logsumexp(logits, dim=2))
+        return torch.stack(rows).contiguous()                              # [NL, Hq, w]
     lses = [window_lse(q, k) for q, k, _ in sets]
 
     def step_lse(i):
-        q, k, v = sets[i % N_SETS]
-        lukv.lukv_evict_lse(cfg, q, k, v, lses[i % N_SETS], wl.n_grid, curves, knots, b_min, b_max, B,
+        q, k, v = sets[i % n_sets]
+        lukv.lukv_evict_lse(cfg, q, k, v, lses[i % n_sets], wl.n_grid, curves, knots, b_min, b_max, B,
                             budgets, offsets, kept, k_out, v_out, None, status, ws)
 
     if args.calibration_copy:
@@ -184,20 +198,20 @@ def main() -> int:
 
     # algorithmic bytes per launch of the two streaming score kernels (8B/32k layer)
     esz = 2
-    k_bytes = Hkv * L * d * esz
-    q_bytes = Hq * w * d * esz
+    k_bytes = NL * Hkv * L * d * esz
+    q_bytes = NL * Hq * w * d * esz
     alg = {"score_stats": k_bytes + q_bytes,
-           "score_accum": k_bytes + q_bytes + Hkv * L * 4}
+           "score_accum": k_bytes + q_bytes + NL * Hkv * L * 4}
     dom = max(alg, key=lambda n: stages[n])
     achieved = alg[dom] / (stages[dom] * 1e-6) / 1e9
     # whole-step algorithmic traffic (streaming model): K twice, Q, scores w+r, idx w+r,
     # gather reads of kept K and V rows, compacted K and V writes
-    b_alg = 2 * k_bytes + q_bytes + 2 * Hkv * L * 4 + 2 * rows * 4 + 2 * rows * d * esz + 2 * rows * d * esz
+    b_alg = 2 * k_bytes + q_bytes + 2 * NL * Hkv * L * 4 + 2 * rows * 4 + 2 * rows * d * esz + 2 * rows * d * esz
     # measured HBM bytes per launch of that kernel: rocprofv3 counter runs of this same command,
     # scaled by the calibration copy, stored beside their summaries (None if not measured)
     traffic, traffic_detail = None, None
     tpath = os.path.join(ROOT, "profiles", "lukv_evict_8b_32k_hbm_traffic.json")
-    if os.path.exists(tpath):
+    if NL == 1 and os.path.exists(tpath):
         rec = json.load(open(tpath)).get(dom)
         if rec:
             traffic = rec["fetch_bytes"] + rec["write_bytes"]
@@ -238,9 +252,13 @@ def main() -> int:
            "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
            "data": "synthetic",
-           "config": {"workload": "8b_32k: 1 layer, 32 q / 8 kv heads, d=128, L=32768, w=32, pool 7, "
-                                  "bf16, B=52428 (20%), 64-point curves; 16 rotating input sets",
-                      "n_input_sets": N_SETS},
+           "config": {"workload": ("8b_32k: 1 layer, 32 q / 8 kv heads, d=128, L=32768, w=32, pool 7, "
+                                   "bf16, B=52428 (20%), 64-point curves; 16 rotating input sets") if NL == 1
+                      else ("%s: %d layers in one call, 32 q / 8 kv heads, d=128, L=32768, w=32, pool 7, bf16, "
+                            "B=%d (20%%) allocated over %d layer-heads; %d input set(s); NOT the headline "
+                            "workload" % (wl.name, NL, rows, NL * Hkv, n_sets)),
+                      "n_input_sets": n_sets, "n_layers": NL,
+                      "layer_tokens_per_s": round(NL * L / (ms_per_step * 1e-3), 1)},
            "roofline": roofline, "cpu_baseline": cpu,
            "lse_variant": {"what": "lukv_evict_lse: window rows' log-sum-exp supplied by the caller, "
                                    "statistics pass over K skipped (other workload, not the headline)",

@@ -134,15 +134,15 @@ __device__ inline void alloc_phase_a(const AllocIO& io, int p, int blk) {
   if (live && part == 0) io.vertex[base + g] = (g == 0 || g == Gp - 1) ? 1 : (steep_in > steep_out ? 1 : 0);
 }
 
-// Phase B for problem p (after phase A's flags are visible).  Any workgroup size that is a
-// multiple of 64 from 256 to 1024; lds: scratch of lds_bytes (>= 32 KiB; with 48 KiB and 1024
-// threads a small problem takes the fast selection), free for this call.
+// Phase B, general form, for problem p (after phase A's flags are visible): any number of heads
+// and segments, any workgroup size that is a multiple of 64 from 256 to 1024; lds: scratch of
+// lds_bytes (>= 32 KiB), free for this call.  Used when alloc_phase_b_mid below does not apply.
 // Everything a thread walks more than once (vertex flags, knots, curves, segments, per-head
 // sums) is staged in LDS when the problem fits (up to 1024 segments and 1024 heads; larger
 // problems use the workspace and global memory, slower but the same arithmetic).  The radix
 // select itself is wave-synchronous on wave 0, its segments held in registers, so a small
 // problem pays no workgroup barrier per digit.
-__device__ inline void alloc_phase_b(const AllocIO& io, int p, char* lds, int lds_bytes) {
+__device__ inline void alloc_phase_b_generic(const AllocIO& io, int p, char* lds, int lds_bytes) {
   constexpr int kRegSegs = 16;              // segments per lane that wave 0 keeps in registers
   const int NH = io.n_heads, Gp = io.n_grid, t = threadIdx.x, nt = blockDim.x;
   const int lane = t & 63, wave = t >> 6;
@@ -491,6 +491,259 @@ __device__ inline void alloc_phase_b(const AllocIO& io, int p, char* lds, int ld
     }
   }
   if (t == 0) io.status[p] = infeasible ? LUKV_ST_INFEASIBLE : 0;
+}
+
+constexpr int kAllocLdsBytes = 61696;   // LDS the 1024-thread form of phase B needs
+
+// Weighted radix select of the threshold key over the problem's segments (key, units), by the
+// whole workgroup of 1024 threads: digits of up to 11 bits over the bits in which the live keys
+// differ (and_keys / or_keys), from the top varying bit down; `want` units are wanted counting
+// from the largest key; stops as soon as the chosen bin holds a single segment.  W is the type
+// that holds unit counts (unsigned when the total fits 31 bits).  Returns (g*, units wanted at
+// g*) through out[0], out[1]; every thread calls it.
+template <class W, class KeyPtr, class WPtr>
+__device__ __forceinline__ void alloc_block_select(KeyPtr skey, WPtr sw, int nseg, unsigned long long and_keys,
+                                                   unsigned long long or_keys, W want, W* bh, unsigned* bc,
+                                                   void* scan_scratch, W* pick, unsigned long long* out) {
+  const int t = threadIdx.x;
+  const unsigned long long differ = and_keys ^ or_keys;
+  int rest = differ ? 64 - __clzll((long long)differ) : 0;     // low bits still open
+  unsigned long long prefix = rest == 64 ? 0ull : and_keys & ~((1ull << rest) - 1ull);
+  bool single = false;
+  while (rest > 0) {
+    const int sh = rest > 11 ? rest - 11 : 0;
+    const unsigned mask = (1u << (rest - sh)) - 1u;
+    const unsigned long long hi_mask = rest == 64 ? 0ull : ~((1ull << rest) - 1ull);
+    __syncthreads();
+    bh[t] = 0; bh[t + 1024] = 0;
+    bc[t] = 0u; bc[t + 1024] = 0u;
+    __syncthreads();
+    for (int i = t; i < nseg; i += 1024) {
+      const unsigned w = sw[i];
+      if (w) {
+        const unsigned long long key = skey[i];
+        if ((key & hi_mask) == (prefix & hi_mask)) {
+          const unsigned d = (unsigned)(key >> sh) & mask;
+          atomicAdd(&bh[d], (W)w);
+          atomicAdd(&bc[d], 1u);
+        }
+      }
+    }
+    __syncthreads();
+    const W a1 = bh[2047 - 2 * t], a0 = bh[2046 - 2 * t];
+    W before;
+    if constexpr (sizeof(W) == 4) {
+      before = block_scan_u32(a1 + a0, reinterpret_cast<unsigned*>(scan_scratch));
+    } else {
+      long long tot;
+      before = (W)block_scan_i64((long long)(a1 + a0), reinterpret_cast<long long*>(scan_scratch), &tot);
+    }
+    if (before < want && want <= before + a1) { pick[0] = (W)(2047 - 2 * t); pick[1] = want - before; }
+    else if (before + a1 < want && want <= before + a1 + a0) { pick[0] = (W)(2046 - 2 * t); pick[1] = want - before - a1; }
+    __syncthreads();
+    const unsigned bin = (unsigned)pick[0];
+    want = pick[1];
+    prefix |= (unsigned long long)bin << sh;
+    rest = sh;
+    if (bc[bin] == 1u) {
+      // a single segment is left in the chosen bin: its key is g*
+      for (int i = t; i < nseg; i += 1024) {
+        const unsigned long long key = skey[i];
+        if (sw[i] && (key >> sh) == (prefix >> sh)) out[0] = key;
+      }
+      single = true;
+      break;
+    }
+  }
+  if (!single && t == 0) out[0] = prefix;
+  if (t == 0) out[1] = (unsigned long long)want;
+}
+
+// Phase B for problems of up to 1024 heads (and 1024 mask words), by a workgroup of 1024
+// threads with kAllocLdsBytes of LDS: vertex flags as bit masks and per-head bounds in LDS;
+// knots, curves and segments too when there are at most 1024 segments, else read from global
+// memory / kept in the workspace; block-wide select; per-head sums by a few threads per head.
+__device__ inline void alloc_phase_b_mid(const AllocIO& io, int p, char* lds) {
+  const int NH = io.n_heads, Gp = io.n_grid, t = threadIdx.x;
+  const int lane = t & 63, wave = t >> 6;
+  const int64_t hbase = (int64_t)p * NH;
+  const int nseg = NH * Gp;
+  const int words = (Gp + 63) / 64;
+  unsigned* spart = reinterpret_cast<unsigned*>(lds);                              // scan scratch (128 B)
+  long long* red = reinterpret_cast<long long*>(lds + 128);                        // sum b_min, units on offer, bad
+  unsigned long long* sel = reinterpret_cast<unsigned long long*>(lds + 160);      // g*, ties, and, or
+  unsigned long long* pick = reinterpret_cast<unsigned long long*>(lds + 192);     // bin, units still wanted
+  unsigned long long* l_mask = reinterpret_cast<unsigned long long*>(lds + 256);   // [NH][words] <= 1024
+  int32_t* l_lb = reinterpret_cast<int32_t*>(lds + 8448);                          // b_min per head
+  int32_t* l_cp = reinterpret_cast<int32_t*>(lds + 12544);                         // cap per head
+  int32_t* l_kn = reinterpret_cast<int32_t*>(lds + 16640);                         // <= 1024 segments:
+  float* l_cu = reinterpret_cast<float*>(lds + 20736);                             //   knots, curves,
+  unsigned* l_w = reinterpret_cast<unsigned*>(lds + 24832);                        //   units and keys
+  unsigned long long* l_key = reinterpret_cast<unsigned long long*>(lds + 28928);
+  char* big = lds + 37120;                                                         // 24 KiB: select, then sums
+  long long* h_gt = reinterpret_cast<long long*>(big);                             // per-head sums
+  long long* h_eq = h_gt + 1024;
+  const int32_t* vtx = io.vertex + hbase * Gp;
+  const int32_t* kn = io.knots + hbase * Gp;
+  const float* cu = io.curves + hbase * Gp;
+  const bool in_lds = nseg <= 1024;
+  auto add = [](unsigned a, unsigned b) { return a + b; };
+  auto band = [](unsigned a, unsigned b) { return a & b; };
+  auto bor = [](unsigned a, unsigned b) { return a | b; };
+
+  __syncthreads();
+  if (t == 0) {
+    red[0] = red[1] = red[2] = 0;
+    sel[0] = 0ull; sel[1] = 0ull; sel[2] = ~0ull; sel[3] = 0ull;
+  }
+  for (int i = t; i < NH * words; i += 1024) l_mask[i] = 0ull;
+  // staging: every global load is issued before the first barrier
+  const bool head = t < NH;
+  const long long lb = head ? io.b_min[hbase + t] : 0;
+  const long long n0 = head ? kn[(int64_t)t * Gp] : 0, n_last = head ? kn[(int64_t)t * Gp + Gp - 1] : 0;
+  const long long bm = head ? io.b_max[hbase + t] : 0;
+  const bool mine = in_lds && t < nseg;
+  const int32_t vk = mine ? kn[t] : 0;
+  const float vc = mine ? cu[t] : 0.f;
+  const int32_t vv = mine ? vtx[t] : 0;
+  __syncthreads();
+  const long long cp = bm < n_last ? bm : n_last;
+  if (head) { l_lb[t] = (int32_t)lb; l_cp[t] = (int32_t)cp; }
+  if (in_lds) {
+    if (mine) {
+      l_kn[t] = vk;
+      l_cu[t] = vc;
+      if (vv) { const int h = t / Gp, g = t - h * Gp; atomicOr(&l_mask[h * words + (g >> 6)], 1ull << (g & 63)); }
+    }
+  } else {
+    for (int i = t; i < nseg; i += 1024)
+      if (vtx[i]) { const int h = i / Gp, g = i - h * Gp; atomicOr(&l_mask[h * words + (g >> 6)], 1ull << (g & 63)); }
+  }
+  // The segments of a head tile (max(b_min, first knot), cap], so the units on offer and the
+  // minimum retention are sums over heads: wave reductions on 16-bit pieces (a lane cannot
+  // overflow), one LDS atomic per wave.
+  if (wave * 64 < NH) {
+    const bool head_bad = head && (lb < 0 || lb > cp);
+    const long long from = lb > n0 ? lb : n0;
+    const unsigned offer = head && !head_bad && cp > from ? (unsigned)(cp - from) : 0u;   // < 2^31
+    const unsigned keep = head && !head_bad ? (unsigned)lb : 0u;
+    const unsigned m_lo = wave_reduce_to_last(keep & 0xFFFFu, 0u, add), m_hi = wave_reduce_to_last(keep >> 16, 0u, add);
+    const unsigned w_lo = wave_reduce_to_last(offer & 0xFFFFu, 0u, add), w_hi = wave_reduce_to_last(offer >> 16, 0u, add);
+    const unsigned long long any_bad = __ballot(head_bad);
+    if (lane == 63) {
+      atomicAdd(reinterpret_cast<unsigned long long*>(&red[0]), ((unsigned long long)m_hi << 16) + m_lo);
+      atomicAdd(reinterpret_cast<unsigned long long*>(&red[1]), ((unsigned long long)w_hi << 16) + w_lo);
+      if (any_bad) atomicAdd(reinterpret_cast<unsigned long long*>(&red[2]), 1ull);
+    }
+  }
+  __syncthreads();
+
+  // one segment per vertex (to the next vertex), clipped to (b_min, cap]
+  unsigned long long* skey = in_lds ? l_key : io.seg_key + hbase * Gp;
+  unsigned* sw = in_lds ? l_w : io.seg_w + hbase * Gp;
+  unsigned long long k_and = ~0ull, k_or = 0ull;
+  bool any_w = false;
+  for (int i = t; i < nseg; i += 1024) {
+    const int h = i / Gp, g = i - h * Gp;
+    const int hb = h * Gp;
+    const unsigned long long* mk = l_mask + h * words;
+    unsigned w = 0;
+    unsigned long long key = 0;
+    if (g < Gp - 1 && ((mk[g >> 6] >> (g & 63)) & 1ull)) {
+      int c = g + 1, wd = c >> 6;            // next vertex; the last knot is always one
+      unsigned long long m = mk[wd] & (~0ull << (c & 63));
+      while (m == 0ull && wd + 1 < words) m = mk[++wd];
+      c = m ? wd * 64 + __ffsll((long long)m) - 1 : Gp - 1;
+      const long long na = in_lds ? l_kn[i] : kn[i], nb = in_lds ? l_kn[hb + c] : kn[hb + c];
+      const double ua = (double)(in_lds ? l_cu[i] : cu[i]), ub = (double)(in_lds ? l_cu[hb + c] : cu[hb + c]);
+      const long long hlb = l_lb[h], hcp = l_cp[h];
+      const long long lo = max(na, hlb), hi = min(nb, hcp);
+      w = hi > lo ? (unsigned)(hi - lo) : 0u;
+      key = gain_key((ub - ua) / (double)(nb - na));
+    }
+    skey[i] = key;
+    sw[i] = w;
+    if (w) { k_and &= key; k_or |= key; any_w = true; }
+  }
+  if (__ballot(any_w) != 0ull) {
+    const unsigned a_lo = wave_reduce_to_last((unsigned)k_and, ~0u, band);
+    const unsigned a_hi = wave_reduce_to_last((unsigned)(k_and >> 32), ~0u, band);
+    const unsigned o_lo = wave_reduce_to_last((unsigned)k_or, 0u, bor);
+    const unsigned o_hi = wave_reduce_to_last((unsigned)(k_or >> 32), 0u, bor);
+    if (lane == 63) {
+      atomicAnd(&sel[2], ((unsigned long long)a_hi << 32) | a_lo);
+      atomicOr(&sel[3], ((unsigned long long)o_hi << 32) | o_lo);
+    }
+  }
+  __syncthreads();
+  const long long R = io.B[p] - red[0];
+  const bool infeasible = red[2] != 0 || R < 0 || R > red[1];
+  const bool active = !infeasible && R > 0;
+  const bool narrow = red[1] < (1ll << 31);     // unit counts fit 32 bits
+
+  // threshold gain g*: W(> g*) < R <= W(>= g*)
+  if (active) {
+    if (narrow)
+      alloc_block_select<unsigned>(skey, sw, nseg, sel[2], sel[3], (unsigned)R, reinterpret_cast<unsigned*>(big),
+                                   reinterpret_cast<unsigned*>(big + 16384), spart, reinterpret_cast<unsigned*>(pick), sel);
+    else
+      alloc_block_select<unsigned long long>(skey, sw, nseg, sel[2], sel[3], (unsigned long long)R,
+                                             reinterpret_cast<unsigned long long*>(big),
+                                             reinterpret_cast<unsigned*>(big + 16384), spart, pick, sel);
+  }
+  __syncthreads();
+  const unsigned long long kstar = sel[0];
+  const long long rem = active ? (long long)sel[1] : 0;
+
+  // budgets: everything above g*, ties at g* in head order.  A power-of-two number of threads
+  // per head sums that head's segments; the parts meet in LDS.
+  for (int h = t; h < NH; h += 1024) { h_gt[h] = 0; h_eq[h] = 0; }
+  __syncthreads();
+  if (active) {
+    int parts = 1;
+    while (parts < 64 && parts * 2 * NH <= 1024) parts *= 2;
+    const int h = t / parts, part = t - h * parts;
+    if (h < NH) {
+      long long gt = 0, eq = 0;
+      for (int e = part; e < Gp; e += parts) {
+        const unsigned w = sw[h * Gp + e];
+        if (w) {
+          const unsigned long long key = skey[h * Gp + e];
+          if (key > kstar) gt += w;
+          else if (key == kstar) eq += w;
+        }
+      }
+      if (gt) atomicAdd(reinterpret_cast<unsigned long long*>(&h_gt[h]), (unsigned long long)gt);
+      if (eq) atomicAdd(reinterpret_cast<unsigned long long*>(&h_eq[h]), (unsigned long long)eq);
+    }
+  }
+  __syncthreads();
+  {
+    const long long gt = head ? h_gt[t] : 0, eq = head ? h_eq[t] : 0;
+    long long eq_before;
+    if (narrow) {
+      eq_before = (long long)block_scan_u32((unsigned)eq, spart);
+    } else {
+      long long tot;
+      eq_before = block_scan_i64(eq, reinterpret_cast<long long*>(spart), &tot);
+    }
+    if (head) {
+      long long take = rem - eq_before;
+      take = take < 0 ? 0 : (take > eq ? eq : take);
+      io.budgets[hbase + t] = (int32_t)(lb + gt + take);
+    }
+  }
+  if (t == 0) io.status[p] = infeasible ? LUKV_ST_INFEASIBLE : 0;
+}
+
+// Phase B for problem p (after phase A's flags are visible); lds: scratch of lds_bytes, free
+// for this call.
+__device__ inline void alloc_phase_b(const AllocIO& io, int p, char* lds, int lds_bytes) {
+  const int words = (io.n_grid + 63) / 64;
+  if (blockDim.x == 1024 && lds_bytes >= kAllocLdsBytes && io.n_heads <= 1024 && io.n_heads * words <= 1024)
+    alloc_phase_b_mid(io, p, lds);
+  else
+    alloc_phase_b_generic(io, p, lds, lds_bytes);
 }
 
 }  // namespace lukv

@@ -9,7 +9,7 @@ __global__ __launch_bounds__(256) void allocate_vertices_kernel(AllocIO io, int 
 }
 
 __global__ __launch_bounds__(1024) void allocate_budgets_kernel(AllocIO io) {
-  __shared__ __align__(16) char lds[49152];
+  __shared__ __align__(16) char lds[kAllocLdsBytes];
   alloc_phase_b(io, blockIdx.x, lds, (int)sizeof(lds));
 }
 

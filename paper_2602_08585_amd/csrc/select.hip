@@ -100,7 +100,7 @@ __global__ __launch_bounds__(1024) void sel_hist_kernel(SelGeom sg, SeqTab tab, 
                                                         float* pooled_out, const float2* range,
                                                         unsigned* hist_parts,
                                                         unsigned long long* by_bin, int32_t* status) {
-  __shared__ __align__(16) char scratch[49152];
+  __shared__ __align__(16) char scratch[kAllocLdsBytes];
   unsigned* lh = reinterpret_cast<unsigned*>(scratch);                      // kHistBins counters
   float* rawt = reinterpret_cast<float*>(scratch + kHistBins * 4);           // slice + pool halo
   unsigned* part = reinterpret_cast<unsigned*>(scratch + kHistBins * 4 + 4352);
