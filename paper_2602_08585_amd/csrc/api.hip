@@ -10,6 +10,20 @@ namespace lukv {
 static inline int64_t align_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
 static inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// compute units of the current device (256 on MI355X), asked once
+static int cu_count() {
+  static int n = 0;
+  if (n == 0) {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+      n = v;
+    else
+      n = 256;
+  }
+  return n;
+}
+
 int validate_config(const lukv_config* cfg, HostCfg* out) {
   if (!cfg || !out || !cfg->cu_seqlens) return LUKV_EINVAL;
   if (cfg->dtype != LUKV_BF16 && cfg->dtype != LUKV_F32) return LUKV_EDTYPE;
@@ -70,6 +84,20 @@ int validate_config(const lukv_config* cfg, HostCfg* out) {
   // keys per score workgroup: at most 64 chunks per head (pass B merges them in its prologue)
   g.chunk_keys = 512;
   while ((max_len + g.chunk_keys - 1) / g.chunk_keys > 64) g.chunk_keys *= 2;
+  // Calls with many workgroups (several layers, long batches) take longer chunks: the prologue of
+  // a score workgroup (queries, first tile, merge of the per-chunk pairs) is then paid once per
+  // 1024 or 2048 keys.  Thresholds in units of the workgroups the chip holds at once (two per
+  // CU), from timings at 1 to 32 layers of 32k context.
+  {
+    const int64_t slots = 2 * (int64_t)cu_count();
+    auto n_wgs = [&](int chunk) {
+      int64_t n = 0;
+      for (int s = 0; s < cfg->n_seqs; ++s) n += (out->seq.cu[s + 1] - out->seq.cu[s] + chunk - 1) / chunk;
+      return n * g.n_kv_heads * g.n_layers;
+    };
+    if (g.chunk_keys < 1024 && n_wgs(1024) >= 2 * slots) g.chunk_keys = 1024;
+    if (g.chunk_keys == 1024 && n_wgs(2048) >= 4 * slots) g.chunk_keys = 2048;
+  }
   out->n_hi = cfg->n_seqs * g.n_layers * g.n_kv_heads;
   return LUKV_OK;
 }
