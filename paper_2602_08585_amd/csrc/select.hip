@@ -64,6 +64,7 @@ struct SelGeom {
   int32_t range_per;      // entries per group
   int32_t range_tail;     // trailing positions without entries (the window, fused path)
   int32_t range_stride;   // entries per head in the range array
+  int32_t slices_per_wg;  // slices one workgroup of sel_hist takes
 };
 
 // (min, max) of the finite scores of every slice, for scores that come from the caller.
@@ -110,8 +111,8 @@ __global__ __launch_bounds__(1024) void sel_hist_kernel(SelGeom sg, SeqTab tab, 
     if (blockIdx.y == 0 && blockIdx.z == 0) alloc_phase_b(aio, blockIdx.x, scratch, (int)sizeof(scratch));
     return;
   }
-  int seq, sl;
-  find_tile(tab, blockIdx.x - n_alloc_blocks, seq, sl);
+  int seq, tile;
+  find_tile(tab, blockIdx.x - n_alloc_blocks, seq, tile);
   const int kvh = blockIdx.y, layer = blockIdx.z, t = threadIdx.x;
   const int lane = t & 63;
   const int tok0 = tab.cu[seq], L = tab.cu[seq + 1] - tok0;
@@ -119,24 +120,10 @@ __global__ __launch_bounds__(1024) void sel_hist_kernel(SelGeom sg, SeqTab tab, 
   const int64_t base = ((int64_t)layer * sg.n_kv_heads + kvh) * sg.total_tokens + tok0;
   const float* src = src_scores + base;
   float* pooled = POOL ? pooled_out + base : nullptr;
-  unsigned* my_part = hist_parts + ((int64_t)hi * sg.max_slices + sl) * (kHistBins / 2);
   // the selection status word starts at zero; later kernels of the call only OR into it
   if (t == 0 && (int)blockIdx.x == n_alloc_blocks && blockIdx.y == 0 && blockIdx.z == 0) *status = 0;
 
-  lh[t] = 0;
-  lh[t + 1024] = 0;
   if (t < 2) rng[t] = t == 0 ? 0xFFFFFFFFu : 0u;
-  const int j0 = sl * kSliceElems, j = j0 + t;
-  const int P = L - sg.window, h = sg.pool_kernel >> 1;
-  float own = 0.f;
-  if (POOL) {
-    for (int i = t; i < kSliceElems + 2 * h; i += 1024) {
-      const int jj = j0 - h + i;
-      rawt[i] = (jj >= 0 && jj < P) ? src[jj] : -INFINITY;
-    }
-  } else if (j < L) {
-    own = src[j];
-  }
   // range of the head's metric: every workgroup of the head folds the same entries
   float mn = INFINITY, mx = -INFINITY;
   {
@@ -155,7 +142,7 @@ __global__ __launch_bounds__(1024) void sel_hist_kernel(SelGeom sg, SeqTab tab, 
       }
     }
   }
-  __syncthreads();   // counters cleared, halo staged
+  __syncthreads();
   if (lane == 0 && mn <= mx) { atomicMin(&rng[0], key_of(mn)); atomicMax(&rng[1], key_of(mx)); }
   __syncthreads();
   unsigned lo = 0u, shift = 21u;   // without a usable range: the top 11 bits of the key
@@ -165,31 +152,51 @@ __global__ __launch_bounds__(1024) void sel_hist_kernel(SelGeom sg, SeqTab tab, 
     lo = rng[0];
     shift = bits > 11 ? (unsigned)(bits - 11) : 0u;
   }
-  float s = own;
-  if (POOL && j < L) {
-    // clipped max-pool over the prefix [0, P); window and sink positions are forced to +inf
-    s = INFINITY;
-    if (j >= sg.n_sink && j < P) {
-      s = rawt[t];
-      for (int d = 1; d <= 2 * h; ++d) s = fmaxf(s, rawt[t + d]);
+  const int P = L - sg.window, h = sg.pool_kernel >> 1;
+  const int n_slices = (L + kSliceElems - 1) / kSliceElems;
+  // a workgroup takes sg.slices_per_wg consecutive slices (more than one in calls with
+  // thousands of slices: fewer, longer workgroups)
+  for (int sl = tile * sg.slices_per_wg; sl < min(n_slices, (tile + 1) * sg.slices_per_wg); ++sl) {
+    unsigned* my_part = hist_parts + ((int64_t)hi * sg.max_slices + sl) * (kHistBins / 2);
+    const int j0 = sl * kSliceElems, j = j0 + t;
+    lh[t] = 0;
+    lh[t + 1024] = 0;
+    float s = 0.f;
+    if (POOL) {
+      for (int i = t; i < kSliceElems + 2 * h; i += 1024) {
+        const int jj = j0 - h + i;
+        rawt[i] = (jj >= 0 && jj < P) ? src[jj] : -INFINITY;
+      }
+    } else if (j < L) {
+      s = src[j];
     }
-    pooled[j] = s;
+    __syncthreads();   // counters cleared, halo staged
+    if (POOL && j < L) {
+      // clipped max-pool over the prefix [0, P); window and sink positions are forced to +inf
+      s = INFINITY;
+      if (j >= sg.n_sink && j < P) {
+        s = rawt[t];
+        for (int d = 1; d <= 2 * h; ++d) s = fmaxf(s, rawt[t + d]);
+      }
+      pooled[j] = s;
+    }
+    const unsigned key = key_of(s), bin = bin_of(key, lo, shift);
+    const unsigned rank = hist_add(lh, bin, j < L);
+    __syncthreads();
+    // suffix counts, descending bins: thread t owns bins 2047-2t and 2046-2t (packed word 1023-t)
+    const unsigned a1 = lh[2047 - 2 * t], a0 = lh[2046 - 2 * t];
+    const unsigned above = block_scan_u32(a1 + a0, part);
+    const unsigned s_hi = above + a1, s_lo = s_hi + a0;          // <= 1024: fit 16 bits
+    my_part[1023 - t] = s_lo | (s_hi << 16);
+    // the slice's (key, position) pairs ordered by descending bin: the keys of bin b sit at
+    // [S[b+1], S[b]), so whoever knows the threshold bin reads its candidates directly
+    __syncthreads();
+    lh[2047 - 2 * t] = above;
+    lh[2046 - 2 * t] = s_hi;
+    __syncthreads();
+    if (j < L) by_bin[base + j0 + lh[bin] + rank] = ((unsigned long long)key << 32) | (unsigned)j;
+    __syncthreads();   // lh and the halo are rewritten by the next slice
   }
-  const unsigned key = key_of(s), bin = bin_of(key, lo, shift);
-  const unsigned rank = hist_add(lh, bin, j < L);
-  __syncthreads();
-  // suffix counts, descending bins: thread t owns bins 2047-2t and 2046-2t (packed word 1023-t)
-  const unsigned a1 = lh[2047 - 2 * t], a0 = lh[2046 - 2 * t];
-  const unsigned above = block_scan_u32(a1 + a0, part);
-  const unsigned s_hi = above + a1, s_lo = s_hi + a0;          // <= 1024: fit 16 bits
-  my_part[1023 - t] = s_lo | (s_hi << 16);
-  // the slice's (key, position) pairs ordered by descending bin: the keys of bin b sit at
-  // [S[b+1], S[b]), so whoever knows the threshold bin reads its candidates directly
-  __syncthreads();
-  lh[2047 - 2 * t] = above;
-  lh[2046 - 2 * t] = s_hi;
-  __syncthreads();
-  if (j < L) by_bin[base + j0 + lh[bin] + rank] = ((unsigned long long)key << 32) | (unsigned)j;
 }
 
 // Exact threshold T among the n_c candidates of the list (the want-th largest, ties included)
@@ -536,7 +543,15 @@ int launch_select_compact(const HostCfg& hc, const WsLayout& lay, const AllocIO*
   SelGeom sg{g.n_layers, g.n_kv_heads, g.total_tokens, lay.max_slices,
              g.window, g.pool_kernel, g.n_sink,
              pool ? g.chunk_keys : kSliceElems, pool ? 4 : 1, pool ? g.window : 0,
-             pool ? lay.max_chunks * 4 : lay.max_slices};
+             pool ? lay.max_chunks * 4 : lay.max_slices, 1};
+  // calls with thousands of slices: a few slices per histogram workgroup (thresholds in units
+  // of the 1024-thread workgroups the chip holds at once, two per CU)
+  {
+    const int64_t n_slice_wgs = (int64_t)tabH.tile0[tabH.n_seqs] * g.n_kv_heads * g.n_layers;
+    if (n_slice_wgs >= 4096) sg.slices_per_wg = 4;
+    else if (n_slice_wgs >= 2048) sg.slices_per_wg = 2;
+  }
+  const SeqTab tabHW = tiles_for(hc.seq, kSliceElems * sg.slices_per_wg, 0);
   unsigned* hist = reinterpret_cast<unsigned*>(ws + lay.hist);
   float2* range = reinterpret_cast<float2*>(ws + lay.range);
   uint4* state = reinterpret_cast<uint4*>(ws + lay.sel_state);
@@ -548,16 +563,16 @@ int launch_select_compact(const HostCfg& hc, const WsLayout& lay, const AllocIO*
   int n_alloc = 0;
   if (aio) { io = *aio; n_alloc = aio->n_problems; }
   const int n_tiles = tabH.tile0[tabH.n_seqs];
-  dim3 gridH(n_tiles + n_alloc, g.n_kv_heads, g.n_layers);
+  dim3 gridH(tabHW.tile0[tabHW.n_seqs] + n_alloc, g.n_kv_heads, g.n_layers);
   dim3 gridR(n_tiles, g.n_kv_heads, g.n_layers);
   dim3 gridE(tabE.tile0[tabE.n_seqs], g.n_kv_heads, g.n_layers);
   stage_mark(kStHist, st);
   if (pool) {
-    hipLaunchKernelGGL(sel_hist_kernel<true>, gridH, dim3(1024), 0, st, sg, tabH, io, n_alloc, scores_in,
+    hipLaunchKernelGGL(sel_hist_kernel<true>, gridH, dim3(1024), 0, st, sg, tabHW, io, n_alloc, scores_in,
                        pooled_out, (const float2*)range, hist, by_bin, status);
   } else {
     hipLaunchKernelGGL(sel_range_kernel, gridR, dim3(1024), 0, st, sg, tabH, scores_in, range);
-    hipLaunchKernelGGL(sel_hist_kernel<false>, gridH, dim3(1024), 0, st, sg, tabH, io, n_alloc, scores_in,
+    hipLaunchKernelGGL(sel_hist_kernel<false>, gridH, dim3(1024), 0, st, sg, tabHW, io, n_alloc, scores_in,
                        (float*)nullptr, (const float2*)range, hist, by_bin, status);
   }
   const float* sel_scores = pool ? pooled_out : scores_in;
