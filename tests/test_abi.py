@@ -83,3 +83,44 @@ def test_synth_budgets_match_named_configs():
     assert synth.workload("8b_full_20").budget_total(0) == 1677721
     assert synth.workload("8b_full_10").budget_total(0) == 838860
     assert synth.workload("long_128k").budget_total(0) == 1677721
+
+
+def test_host_refusals_of_the_profile_and_lse_entry_points():
+    """Nothing here reaches a kernel: bad dimensions, null pointers and unordered grids are
+    refused on the host."""
+    lib = lukv.load_library()
+    out = ctypes.c_int64(0)
+    assert lib.lukv_profile_workspace_bytes(0, 8, 64, ctypes.byref(out)) == lukv.LUKV_EINVAL
+    assert lib.lukv_profile_workspace_bytes(65, 8, 64, ctypes.byref(out)) == lukv.LUKV_EINVAL
+    assert lib.lukv_profile_workspace_bytes(3, 8, 64, ctypes.byref(out)) == lukv.LUKV_OK and out.value > 0
+    rho_bad = (ctypes.c_double * 3)(0.0, 0.5, 0.5)
+    rho_ok = (ctypes.c_double * 3)(0.0, 0.5, 1.0)
+    fake = ctypes.c_void_p(256)       # never dereferenced: the calls below are refused first
+    assert lib.lukv_profile_build(3, 8, 64, fake, fake, fake, fake, 4096, 3, rho_bad, fake, fake, 1 << 30,
+                                  None) == lukv.LUKV_EINVAL
+    assert lib.lukv_profile_build(3, 8, 64, fake, fake, fake, fake, 4096, 3, rho_ok, fake, fake, 16,
+                                  None) == lukv.LUKV_EWORKSPACE
+    assert lib.lukv_budgets_from_profile(8, 3, rho_bad, fake, 0.5, 4096, fake, fake, fake, fake,
+                                         None) == lukv.LUKV_EINVAL
+    assert lib.lukv_budgets_from_profile(8, 3, rho_ok, None, 0.5, 4096, fake, fake, fake, fake,
+                                         None) == lukv.LUKV_EINVAL
+    assert lib.lukv_budgets_from_profile(8, 3, rho_ok, fake, float("nan"), 4096, fake, fake, fake, fake,
+                                         None) == lukv.LUKV_EINVAL
+    c = _cfg().to_c()
+    assert lib.lukv_score_lse(ctypes.byref(c), fake, fake, None, fake, fake, 1 << 40, None) == lukv.LUKV_EINVAL
+    assert lib.lukv_evict_budgets(ctypes.byref(c), fake, fake, fake, None, None, fake, 10, fake, fake, fake,
+                                  None, fake, fake, 1 << 40, None) == lukv.LUKV_EINVAL
+
+
+def test_sequences_longer_than_the_limit_are_refused():
+    with pytest.raises(lukv.LukvError):
+        lukv.lukv_workspace_bytes(_cfg(cu_seqlens=[0, (1 << 20) + 1], stride_head=((1 << 20) + 1) * 128,
+                                       stride_layer=8 * ((1 << 20) + 1) * 128), 64)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True,
+                       text=True, timeout=120)
+    assert r.returncode == 2 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
