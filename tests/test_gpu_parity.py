@@ -42,6 +42,18 @@ def small(name):
         "f32_d128": dict(n_q_heads=4, n_kv_heads=2, head_dim=128, seq_lens=[900], window=32, dtype=synth.F32),
         "f32_d64_peaky": dict(n_q_heads=8, n_kv_heads=4, head_dim=64, seq_lens=[1024], window=16,
                               dtype=synth.F32, q_gain=64.0),
+        # rows = 512, the largest G*w: four wave groups take the row blocks in turn
+        "bf16_g8_w64_rows512": dict(n_q_heads=8, n_kv_heads=1, head_dim=128, seq_lens=[1500], window=64),
+        # multi-head attention (G = 1), no pooling (kernel 1), no sink
+        "bf16_mha_pool1_nosink": dict(n_q_heads=2, n_kv_heads=2, head_dim=128, seq_lens=[700], window=32,
+                                      pool_kernel=1, n_sink=0),
+        # widest pooling window the library takes
+        "bf16_pool31": dict(n_q_heads=8, n_kv_heads=2, head_dim=64, seq_lens=[900], window=16, pool_kernel=31),
+        # float32 with head_dim 128 at its row limit (256)
+        "f32_d128_rows256": dict(n_q_heads=8, n_kv_heads=1, head_dim=128, seq_lens=[600], window=32,
+                                 dtype=synth.F32),
+        # a one-token observation window (rows = G, padded to one 32-row block)
+        "bf16_w1": dict(n_q_heads=4, n_kv_heads=1, head_dim=128, seq_lens=[300], window=1, n_sink=2),
         # shortest legal context: one prefix token beyond window + sink
         "bf16_short": dict(n_q_heads=4, n_kv_heads=1, head_dim=128, seq_lens=[37], window=32, n_sink=4,
                            keep_ratio=1.0, n_grid=4),
@@ -54,7 +66,8 @@ def small(name):
 
 
 SMALL = ["bf16_g4_w32", "bf16_g5_w32", "bf16_g4_w64", "bf16_g7_w16_d64", "bf16_ragged", "f32_d128",
-         "f32_d64_peaky", "bf16_short"]
+         "f32_d64_peaky", "bf16_short", "bf16_g8_w64_rows512", "bf16_mha_pool1_nosink", "bf16_pool31",
+         "f32_d128_rows256", "bf16_w1"]
 
 
 def _problem(name):
@@ -546,3 +559,33 @@ def test_online_mode_profile_lookup_then_evict(use_lse):
                 check_band(kept[a:b], O.select(S[c], int(budgets_h[hi])), S[c], BAND)
                 assert np.array_equal(ko[a:b], p.data["k"][l, c, cu[s]:cu[s + 1]][kept[a:b]])
                 assert np.array_equal(vo[a:b], p.data["v"][l, c, cu[s]:cu[s + 1]][kept[a:b]])
+
+
+def test_strided_inputs_and_custom_scale():
+    """K, V and Q that are views into wider buffers (token stride > head_dim, padded heads), and a
+    softmax scale other than 1/sqrt(d)."""
+    print("case strided", flush=True)
+    wl = small("bf16_g4_w32")
+    p = Problem(wl)
+    NL, H, T, d = p.k.shape
+    kbig = torch.zeros((NL, H + 1, T + 5, 2 * d), dtype=p.k.dtype, device="cuda")
+    vbig = torch.zeros_like(kbig)
+    kv, vv = kbig[:, 1:, 3:3 + T, d:], vbig[:, 1:, 3:3 + T, d:]        # data_ptr 16-byte aligned, strided
+    kv.copy_(p.k)
+    vv.copy_(p.v)
+    qbig = torch.zeros((NL, wl.n_q_heads, wl.n_seqs * wl.window + 2, 3 * d), dtype=p.q.dtype, device="cuda")
+    qv = qbig[:, :, 1:1 + wl.n_seqs * wl.window, d:2 * d]
+    qv.copy_(p.q)
+    scale = 0.05
+    cfg = lukv.Config.for_tensors(qv, kv, wl.window, wl.cu_seqlens.tolist(), wl.pool_kernel, wl.n_sink,
+                                  softmax_scale=scale)
+    assert cfg.stride_tok == 2 * d and cfg.qstride_tok == 3 * d
+    ws = lukv.alloc_workspace(lukv.lukv_workspace_bytes(cfg, wl.n_grid))
+    out = p.new_outputs()
+    lukv.lukv_evict(cfg, qv, kv, vv, wl.n_grid, p.curves, p.knots, p.b_min, p.b_max, p.B, out["budgets"],
+                    out["offsets"], out["kept_idx"], out["k_out"], out["v_out"], out["pooled"], out["status"], ws)
+    torch.cuda.synchronize()
+    a = p.alloc
+    ref = O.evict(p.data["q_win"], p.data["k"], p.data["v"], wl.cu_seqlens, wl.n_kv_heads, wl.window,
+                  wl.pool_kernel, wl.n_sink, a["curves"], a["knots"], a["b_min"], a["b_max"], a["B"], scale=scale)
+    assert _check_evict(p, out, ref) == 0
