@@ -53,8 +53,8 @@ def main() -> int:
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE counters (profiles/)")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.stderr.write("bench.py: this build runs on ONE GPU only (the path shards without "
-                         "communication; see DESIGN.md); --gpus %d is not supported\n" % args.gpus)
+        sys.stderr.write("bench.py: this build runs on ONE GPU only (the path shards over heads and "
+                         "layers without communication); --gpus %d is not supported\n" % args.gpus)
         return 2
 
     import numpy as np

@@ -11,7 +11,9 @@ A plain, slow, fp64 statement of what the path computes, written from the paper:
              fixed deterministic tie rule App. A.1 assumes (lowest index first);
   compact  - Sec. 3.2 / Eq. 3: the retained index set I_{l,h} as a dense per-head cache;
   profile  - Sec. 4.3, Eq. 11 and "Online Execution": the static table of local ratios over a
-             grid of global ratios, and the look-up that turns a target ratio into budgets.
+             grid of global ratios, and the look-up that turns a target ratio into budgets;
+  decode   - Sec. 3.2, Eq. 3: a decode step's attention over the retained entries (the consumer
+             of the compacted cache).
 
 Only tests, the smoke check and the benchmark's cpu_baseline leg may import this
 module.  It shares no code with the HIP path and never calls it.
@@ -290,6 +292,28 @@ def select(s: np.ndarray, k: int) -> np.ndarray:
 def compact(x: np.ndarray, idx: np.ndarray) -> np.ndarray:
     """Rows idx of x [L, d], bit for bit, in the given order."""
     return x[idx].copy()
+
+
+# ----------------------------------------------------------------------------
+# consumer of the compacted cache: one decode step (Sec. 3.2, Eq. 3)
+# ----------------------------------------------------------------------------
+
+def decode_attention(q: np.ndarray, k_rows: np.ndarray, v_rows: np.ndarray,
+                     scale: float | None = None) -> np.ndarray:
+    """Attention of decode queries over the retained entries of one KV head (Eq. 3 restricted to
+    the index set I_{l,h}): out[g] = softmax_r(scale * q[g] . k_rows[r]) @ v_rows.
+
+    q [G, d] (the query heads of the group), k_rows, v_rows [n, d], all float64.  Returns
+    [G, d] float64.  n = 0 gives zeros (nothing to attend to)."""
+    G, d = q.shape
+    if scale is None:
+        scale = 1.0 / math.sqrt(d)
+    if k_rows.shape[0] == 0:
+        return np.zeros((G, d), dtype=np.float64)
+    s = scale * (q @ k_rows.T)                                  # [G, n]
+    p = np.exp(s - s.max(axis=1, keepdims=True))
+    p = p / p.sum(axis=1, keepdims=True)
+    return p @ v_rows
 
 
 # ----------------------------------------------------------------------------

@@ -16,7 +16,7 @@ from tests import test_oracle_score as TS
 
 PUBLIC = ["window_attention_sum", "window_lse", "max_pool_1d", "score", "concave_hull", "marginal_gains",
           "_gain_of_unit", "_slope", "allocate", "select", "compact", "offsets_of", "profile_build",
-          "budgets_from_profile"]
+          "budgets_from_profile", "decode_attention"]
 
 MUTANTS = {
     # name: (snippet, replacement, pin that must fail)
@@ -57,6 +57,13 @@ MUTANTS = {
                                        lambda: TA.test_handworked_profile_and_lookup()),
     "lookup_no_interpolation": ("r = lo + t * (hi - lo)", "r = lo",
                                 lambda: TA.test_handworked_profile_and_lookup()),
+    "decode_softmax_over_queries": ("p = p / p.sum(axis=1, keepdims=True)\n    return p @ v_rows",
+                                    "p = p / p.sum(axis=0, keepdims=True)\n    return p @ v_rows",
+                                    lambda: TS.test_decode_attention_library_cross_check()),
+    "decode_missing_scale": ("scale = 1.0 / math.sqrt(d)\n    if k_rows.shape[0] == 0:", "scale = 1.0\n    if k_rows.shape[0] == 0:",
+                             lambda: TS.test_decode_attention_library_cross_check()),
+    "decode_values_for_keys": ("return p @ v_rows", "return p @ k_rows",
+                               lambda: TS.test_decode_attention_handworked_and_special_cases()),
     "sink_not_forced": ("s[:, :min(n_sink, L)] = np.inf", "pass",
                         lambda: TS.test_brute_force_definition()),
     "hull_keeps_collinear": ("if steepness_in > steepness_out:", "if steepness_in >= steepness_out:",

@@ -186,3 +186,31 @@ def test_bf16_decode_exact():
 def test_window_not_longer_than_context():
     with pytest.raises(ValueError):
         O.score(np.ones((1, 4, 2)), np.ones((1, 4, 2)), 1, 4, 3, 0)
+
+
+# --- decode-step attention over retained entries (Eq. 3) -------------------------------------
+
+def test_decode_attention_handworked_and_special_cases():
+    # two retained entries, logits ln 1 and ln 3 (scale 1): weights 1/4 and 3/4
+    q = np.array([[1.0, 0.0]])
+    k = np.array([[0.0, 5.0], [math.log(3.0), -2.0]])
+    v = np.array([[4.0, 0.0], [0.0, 8.0]])
+    assert np.allclose(O.decode_attention(q, k, v, scale=1.0), [[1.0, 6.0]], rtol=1e-15)
+    # a single retained entry returns its value row; equal keys average the values
+    assert np.array_equal(O.decode_attention(q, k[:1], v[:1], scale=1.0), v[:1])
+    same = np.tile(k[:1], (5, 1))
+    vals = np.arange(10.0).reshape(5, 2)
+    assert np.allclose(O.decode_attention(q, same, vals), vals.mean(axis=0)[None], rtol=1e-15)
+    assert np.array_equal(O.decode_attention(q, k[:0], v[:0]), np.zeros((1, 2)))
+
+
+def test_decode_attention_library_cross_check():
+    rng = np.random.default_rng(21)
+    G, n, d = 4, 37, 16
+    q, k, v = rng.standard_normal((G, d)), rng.standard_normal((n, d)), rng.standard_normal((n, d))
+    got = O.decode_attention(q, k, v)
+    ref = torch.nn.functional.scaled_dot_product_attention(torch.from_numpy(q)[None], torch.from_numpy(k)[None],
+                                                           torch.from_numpy(v)[None])[0].numpy()
+    assert np.allclose(got, ref, rtol=1e-12, atol=1e-14)
+    # every output row is a convex combination of the value rows
+    assert np.all(got <= v.max(axis=0) + 1e-12) and np.all(got >= v.min(axis=0) - 1e-12)
