@@ -195,6 +195,22 @@ int lukv_evict_budgets(const lukv_config* cfg, const void* q_win, const void* k,
                        int64_t out_rows, int32_t* kept_idx, void* k_out, void* v_out, float* pooled,
                        int32_t* status, void* ws, int64_t ws_bytes, void* stream);
 
+/* Consumer of the compacted cache: one decode step's attention over the retained entries of
+ * every head (Sec. 3.2, Eq. 3 restricted to the retained index sets).  For head hi and each of
+ * the G query heads of its group: out = softmax_r(softmax_scale * q . K_r) V over the packed rows
+ * r in [offsets[hi], offsets[hi+1]); zeros for a head without rows.  fp32 accumulation.
+ *   cfg      dimensions, dtype, cu_seqlens (for the longest sequence) and softmax_scale as above;
+ *            n_q_heads / n_kv_heads <= 16
+ *   q_dec    device, dtype, contiguous [n_layers][n_q_heads][n_seqs][head_dim]: one query per
+ *            sequence and query head
+ *   k_packed, v_packed, offsets as written by lukv_evict / lukv_select_compact
+ *   out      device float32, contiguous [n_layers][n_q_heads][n_seqs][head_dim]
+ *   ws       lukv_decode_workspace_bytes(cfg) bytes, 256-byte aligned. */
+int lukv_decode_workspace_bytes(const lukv_config* cfg, int64_t* bytes);
+int lukv_decode_attention(const lukv_config* cfg, const void* q_dec, const void* k_packed,
+                          const void* v_packed, const int64_t* offsets, float* out, void* ws,
+                          int64_t ws_bytes, void* stream);
+
 /* Instrumentation for benchmarks (process-wide, not thread-safe; for callers that time the path,
  * not part of the method).  While n_events > 0, every call records events[i] (hipEvent_t, created
  * by the caller, passed as void*) on its stream immediately before stage i, and lukv_evict records

@@ -402,6 +402,30 @@ int lukv_evict_budgets(const lukv_config* cfg, const void* q_win, const void* k,
   return rc;
 }
 
+int lukv_decode_workspace_bytes(const lukv_config* cfg, int64_t* bytes) {
+  if (!bytes) return LUKV_EINVAL;
+  HostCfg hc;
+  const int rc = validate_config(cfg, &hc);
+  if (rc) return rc;
+  if (hc.g.group > 16) return LUKV_EINVAL;
+  *bytes = align_up(decode_workspace_bytes(hc), 256);
+  return LUKV_OK;
+}
+
+int lukv_decode_attention(const lukv_config* cfg, const void* q_dec, const void* k_packed,
+                          const void* v_packed, const int64_t* offsets, float* out, void* ws,
+                          int64_t ws_bytes, void* stream) {
+  HostCfg hc;
+  const int rc = validate_config(cfg, &hc);
+  if (rc) return rc;
+  if (hc.g.group > 16) return LUKV_EINVAL;
+  if (!q_dec || !k_packed || !v_packed || !offsets || !out) return LUKV_EINVAL;
+  if (!aligned16(k_packed) || !aligned16(v_packed)) return LUKV_EINVAL;
+  if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u) || ws_bytes < decode_workspace_bytes(hc))
+    return LUKV_EWORKSPACE;
+  return launch_decode(hc, q_dec, k_packed, v_packed, offsets, out, (char*)ws, static_cast<hipStream_t>(stream));
+}
+
 int lukv_set_stage_events(void* const* events, int32_t n_events) {
   if (n_events < 0 || (n_events > 0 && !events)) return LUKV_EINVAL;
   g_stage_events = n_events ? events : nullptr;

@@ -1,0 +1,260 @@
+// Consumer of the compacted cache: one decode step's attention over the retained entries of
+// every head (Sec. 3.2, Eq. 3 restricted to the index set I_{l,h}).  The packed K and V rows of
+// head hi sit at [offsets[hi], offsets[hi+1]); the G query heads of a group share them.
+//   decode_partial - one workgroup per (head, block of rows): K tile through LDS, one row per
+//                    thread for the G logits, block softmax statistics, then the V tile through
+//                    the same LDS buffer and p-weighted column sums; leaves (max, sum, weighted
+//                    values) per query head.
+//   decode_combine - one workgroup per (query head, head): merges the blocks' partial results.
+// Row counts live on the device (they are budgets), so the grid covers the longest possible
+// head and workgroups beyond a head's rows exit at once.
+#include "lukv_internal.hpp"
+
+namespace lukv {
+
+constexpr int kDecMaxGroup = 16;   // query heads per KV head the decode kernels take
+
+struct DecGeom {
+  int32_t n_layers, n_q_heads, n_kv_heads, group, n_seqs, max_blocks;
+  float scale;
+};
+
+template <bool F32>
+__device__ __forceinline__ void unpack8(const u32x4& v, float (&f)[8]);
+
+template <>
+__device__ __forceinline__ void unpack8<false>(const u32x4& v, float (&f)[8]) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    f[2 * i] = __uint_as_float(v[i] << 16);
+    f[2 * i + 1] = __uint_as_float(v[i] & 0xFFFF0000u);
+  }
+}
+
+// R rows per block; a row is D elements = kRowU4 16-byte pieces, padded by one piece in LDS.
+template <bool F32, int D, int R>
+__global__ __launch_bounds__(256) void decode_partial_kernel(DecGeom g, const char* q, const char* kp,
+                                                             const char* vp, const int64_t* offsets,
+                                                             float* part) {
+  constexpr int kEsize = F32 ? 4 : 2;
+  constexpr int kRowU4 = D * kEsize / 16;
+  constexpr int kLdsRowU4 = kRowU4 + 1;
+  constexpr int kLoads = R * kRowU4 / 256;
+  constexpr int kPerU4 = 16 / kEsize;            // elements in one 16-byte piece
+  __shared__ u32x4 tile[R * kLdsRowU4];
+  __shared__ float qs[kDecMaxGroup * D];
+  __shared__ float ps[kDecMaxGroup * R];
+  __shared__ float red[4][kDecMaxGroup];
+  __shared__ float stat[2][kDecMaxGroup];
+  const int hi = blockIdx.y, blk = blockIdx.x, t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int64_t row_begin = offsets[hi] + (int64_t)blk * R;
+  const int64_t rows_left = offsets[hi + 1] - row_begin;
+  if (rows_left <= 0) return;
+  const int n = rows_left < R ? (int)rows_left : R;
+  const int G = g.group;
+  const int kvh = hi % g.n_kv_heads, layer = (hi / g.n_kv_heads) % g.n_layers;
+  const int seq = hi / (g.n_kv_heads * g.n_layers);
+
+  // K and V tiles: 16 bytes per lane, rows beyond the block clamped to its last row
+  u32x4 kr[kLoads], vr[kLoads];
+#pragma unroll
+  for (int u = 0; u < kLoads; ++u) {
+    const int i = u * 256 + t, r = i / kRowU4, c = i % kRowU4;
+    const int64_t row = row_begin + (r < n ? r : n - 1);
+    kr[u] = *reinterpret_cast<const u32x4*>(kp + (row * kRowU4 + c) * 16);
+    vr[u] = *reinterpret_cast<const u32x4*>(vp + (row * kRowU4 + c) * 16);
+  }
+  // the group's decode queries as floats
+  for (int i = t; i < G * D; i += 256) {
+    const int gq = i / D, x = i - gq * D;
+    const int64_t qi = (((int64_t)layer * g.n_q_heads + kvh * G + gq) * g.n_seqs + seq) * D + x;
+    qs[i] = F32 ? reinterpret_cast<const float*>(q)[qi]
+                : __uint_as_float((unsigned)reinterpret_cast<const unsigned short*>(q)[qi] << 16);
+  }
+#pragma unroll
+  for (int u = 0; u < kLoads; ++u) {
+    const int i = u * 256 + t;
+    tile[(i / kRowU4) * kLdsRowU4 + i % kRowU4] = kr[u];
+  }
+  __syncthreads();
+
+  // logits of this thread's row (R = 128 rows: the first two waves)
+  float s[kDecMaxGroup];
+#pragma unroll
+  for (int gq = 0; gq < kDecMaxGroup; ++gq) s[gq] = 0.f;
+  if (t < R) {
+    for (int c = 0; c < kRowU4; ++c) {
+      const u32x4 kv = tile[t * kLdsRowU4 + c];
+      float kf[8];
+      if constexpr (F32) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) kf[e] = __uint_as_float(kv[e]);
+      } else {
+        unpack8<false>(kv, kf);
+      }
+#pragma unroll
+      for (int gq = 0; gq < kDecMaxGroup; ++gq) {
+        if (gq < G) {
+          const float* qv = qs + gq * D + c * kPerU4;
+#pragma unroll
+          for (int e = 0; e < kPerU4; ++e) s[gq] = fmaf(qv[e], kf[e], s[gq]);
+        }
+      }
+    }
+  }
+  const bool live = t < n;
+  // block maximum and sum of exponentials per query head
+#pragma unroll
+  for (int gq = 0; gq < kDecMaxGroup; ++gq) {
+    if (gq < G) {
+      float m = live ? s[gq] * g.scale : -INFINITY;
+      s[gq] = m;
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+      if (lane == 0) red[wave][gq] = m;
+    }
+  }
+  __syncthreads();
+  if (t < G) stat[0][t] = fmaxf(fmaxf(red[0][t], red[1][t]), fmaxf(red[2][t], red[3][t]));
+  __syncthreads();
+#pragma unroll
+  for (int gq = 0; gq < kDecMaxGroup; ++gq) {
+    if (gq < G) {
+      const float p = live ? __expf(s[gq] - stat[0][gq]) : 0.f;
+      if (t < R) ps[gq * R + t] = p;
+      float l = p;
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) l += __shfl_xor(l, o);
+      if (lane == 0) red[wave][gq] = l;
+    }
+  }
+  // the V tile takes the K tile's place (every thread is done reading K)
+  __syncthreads();
+  if (t < G) stat[1][t] = (red[0][t] + red[1][t]) + (red[2][t] + red[3][t]);
+#pragma unroll
+  for (int u = 0; u < kLoads; ++u) {
+    const int i = u * 256 + t;
+    tile[(i / kRowU4) * kLdsRowU4 + i % kRowU4] = vr[u];
+  }
+  __syncthreads();
+
+  // p-weighted column sums: one (query head, pair of columns) at a time per thread
+  float* my_part = part + ((int64_t)hi * g.max_blocks + blk) * G * (D + 2);
+  const unsigned* tile32 = reinterpret_cast<const unsigned*>(tile);
+  constexpr int kCols = F32 ? 1 : 2;             // columns in one 32-bit word
+  constexpr int kWords = D / kCols;
+  for (int o = t; o < G * kWords; o += 256) {
+    const int gq = o / kWords, wd = o - gq * kWords;
+    const float* pg = ps + gq * R;
+    float a0 = 0.f, a1 = 0.f;
+    for (int r = 0; r < n; ++r) {
+      const unsigned w = tile32[r * (kLdsRowU4 * 4) + wd];
+      const float p = pg[r];
+      if constexpr (F32) {
+        a0 = fmaf(p, __uint_as_float(w), a0);
+      } else {
+        a0 = fmaf(p, __uint_as_float(w << 16), a0);
+        a1 = fmaf(p, __uint_as_float(w & 0xFFFF0000u), a1);
+      }
+    }
+    my_part[gq * (D + 2) + wd * kCols] = a0;
+    if constexpr (!F32) my_part[gq * (D + 2) + wd * kCols + 1] = a1;
+  }
+  if (t < G) {
+    my_part[t * (D + 2) + D] = stat[0][t];
+    my_part[t * (D + 2) + D + 1] = stat[1][t];
+  }
+}
+
+// One workgroup per (query head of the group, head): the blocks' partial results are merged with
+// weights exp(m_b - M); D threads own the columns, 256 / D groups of them share the blocks.
+template <int D, int R>
+__global__ __launch_bounds__(256) void decode_combine_kernel(DecGeom g, const int64_t* offsets, const float* part,
+                                                             float* out) {
+  constexpr int NP = 256 / D;
+  __shared__ float red[4];
+  __shared__ float wts[256];
+  __shared__ float accs[NP][D];
+  const int gq = blockIdx.x, hi = blockIdx.y, t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int G = g.group;
+  const int kvh = hi % g.n_kv_heads, layer = (hi / g.n_kv_heads) % g.n_layers;
+  const int seq = hi / (g.n_kv_heads * g.n_layers);
+  const int64_t rows = offsets[hi + 1] - offsets[hi];
+  const int n_blk = (int)((rows + R - 1) / R);
+  const float* hp = part + ((int64_t)hi * g.max_blocks * G + gq) * (D + 2);
+  const int64_t bstride = (int64_t)G * (D + 2);
+  const int x = t % D, pt = t / D;
+  float* dst = out + (((int64_t)layer * g.n_q_heads + kvh * G + gq) * g.n_seqs + seq) * D;
+  if (n_blk == 0) {
+    if (t < D) dst[t] = 0.f;
+    return;
+  }
+  float m = -INFINITY;
+  for (int b = t; b < n_blk; b += 256) m = fmaxf(m, hp[b * bstride + D]);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+  if (lane == 0) red[wave] = m;
+  __syncthreads();
+  const float M = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+  float l = 0.f, a = 0.f;
+  for (int b0 = 0; b0 < n_blk; b0 += 256) {
+    __syncthreads();
+    float e = 0.f;
+    if (b0 + t < n_blk) {
+      e = __expf(hp[(b0 + t) * bstride + D] - M);
+      l += hp[(b0 + t) * bstride + D + 1] * e;
+    }
+    wts[t] = e;
+    __syncthreads();
+    const int nb = n_blk - b0 < 256 ? n_blk - b0 : 256;
+#pragma unroll 4
+    for (int bb = pt; bb < nb; bb += NP) a = fmaf(hp[(b0 + bb) * bstride + x], wts[bb], a);
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) l += __shfl_xor(l, o);
+  __syncthreads();
+  if (lane == 0) red[wave] = l;
+  accs[pt][x] = a;
+  __syncthreads();
+  if (t < D) {
+    float tot = 0.f;
+#pragma unroll
+    for (int q2 = 0; q2 < NP; ++q2) tot += accs[q2][t];
+    dst[t] = tot / ((red[0] + red[1]) + (red[2] + red[3]));
+  }
+}
+
+int decode_rows_per_block(const HostCfg&) { return 128; }
+
+int64_t decode_workspace_bytes(const HostCfg& hc) {
+  const int R = decode_rows_per_block(hc);
+  const int64_t max_blocks = (hc.max_len + R - 1) / R;
+  return (int64_t)hc.n_hi * max_blocks * hc.g.group * (hc.g.head_dim + 2) * 4;
+}
+
+template <bool F32, int D, int R>
+static int launch_decode_t(const HostCfg& hc, const void* q, const void* kp, const void* vp,
+                           const int64_t* offsets, float* out, char* ws, hipStream_t st) {
+  const Geom& g = hc.g;
+  DecGeom dg{g.n_layers, g.n_q_heads, g.n_kv_heads, g.group, hc.seq.n_seqs, (hc.max_len + R - 1) / R,
+             g.scale_log2e * 0.69314718055994530942f};
+  float* part = reinterpret_cast<float*>(ws);
+  hipLaunchKernelGGL((decode_partial_kernel<F32, D, R>), dim3(dg.max_blocks, hc.n_hi), dim3(256), 0, st, dg,
+                     (const char*)q, (const char*)kp, (const char*)vp, offsets, part);
+  hipLaunchKernelGGL((decode_combine_kernel<D, R>), dim3(g.group, hc.n_hi), dim3(256), 0, st, dg, offsets,
+                     (const float*)part, out);
+  return check_launch();
+}
+
+int launch_decode(const HostCfg& hc, const void* q, const void* kp, const void* vp, const int64_t* offsets,
+                  float* out, char* ws, hipStream_t st) {
+  const Geom& g = hc.g;
+  if (g.group > kDecMaxGroup) return LUKV_EINVAL;
+  if (!g.f32 && g.head_dim == 128) return launch_decode_t<false, 128, 128>(hc, q, kp, vp, offsets, out, ws, st);
+  if (!g.f32 && g.head_dim == 64) return launch_decode_t<false, 64, 128>(hc, q, kp, vp, offsets, out, ws, st);
+  if (g.f32 && g.head_dim == 128) return launch_decode_t<true, 128, 128>(hc, q, kp, vp, offsets, out, ws, st);
+  if (g.f32 && g.head_dim == 64) return launch_decode_t<true, 64, 128>(hc, q, kp, vp, offsets, out, ws, st);
+  return LUKV_EDTYPE;
+}
+
+}  // namespace lukv

@@ -99,6 +99,11 @@ int launch_profile_lookup(const float* row_lo, const float* row_hi, double t, in
                           const int32_t* b_min, const int32_t* b_max, int32_t* budgets, int64_t* offsets,
                           hipStream_t st);
 
+// decode-step attention over the packed cache (decode.hip)
+int64_t decode_workspace_bytes(const HostCfg& hc);
+int launch_decode(const HostCfg& hc, const void* q, const void* kp, const void* vp, const int64_t* offsets,
+                  float* out, char* ws, hipStream_t st);
+
 // Optional instrumentation (lukv_set_stage_events): record the caller's event for a stage.
 enum Stage { kStAllocate = 0, kStStats, kStAccum, kStPool, kStHist, kStTail, kStEmit, kStEnd,
              kNumStageEvents };

@@ -34,7 +34,8 @@ LUKV_ST_CLAMPED = 2
 EXPORTS = ("lukv_workspace_bytes", "lukv_allocate_workspace_bytes", "lukv_score", "lukv_allocate",
            "lukv_select_compact", "lukv_evict", "lukv_score_lse", "lukv_evict_lse",
            "lukv_profile_workspace_bytes", "lukv_profile_build", "lukv_budgets_from_profile",
-           "lukv_evict_budgets", "lukv_set_stage_events", "lukv_stage_name", "lukv_strerror")
+           "lukv_evict_budgets", "lukv_decode_workspace_bytes", "lukv_decode_attention",
+           "lukv_set_stage_events", "lukv_stage_name", "lukv_strerror")
 LUKV_STAGE_END = 7
 LUKV_NUM_STAGE_EVENTS = 8
 
@@ -86,6 +87,8 @@ def load_library() -> ctypes.CDLL:
     lib.lukv_profile_build.argtypes = [I32, I32, I32, P, P, P, P, I32, I32, F64P, P, P, I64, P]
     lib.lukv_budgets_from_profile.argtypes = [I32, I32, F64P, P, ctypes.c_double, I32, P, P, P, P, P]
     lib.lukv_evict_budgets.argtypes = [CP, P, P, P, P, P, P, I64, P, P, P, P, P, P, I64, P]
+    lib.lukv_decode_workspace_bytes.argtypes = [CP, ctypes.POINTER(I64)]
+    lib.lukv_decode_attention.argtypes = [CP, P, P, P, P, P, P, I64, P]
     lib.lukv_set_stage_events.argtypes = [ctypes.POINTER(ctypes.c_void_p), I32]
     lib.lukv_stage_name.argtypes = [I32]
     lib.lukv_stage_name.restype = ctypes.c_char_p
@@ -292,6 +295,19 @@ def lukv_evict_budgets(cfg: Config, q_win, k, v, lse, budgets, offsets, out_rows
                                              _ptr(kept_idx), _ptr(k_out), _ptr(v_out), _ptr(pooled),
                                              _ptr(status), _ptr(ws), ws.numel(), _stream(stream)),
            "lukv_evict_budgets")
+
+
+def lukv_decode_workspace_bytes(cfg: Config) -> int:
+    out = ctypes.c_int64(0)
+    _check(load_library().lukv_decode_workspace_bytes(ctypes.byref(cfg.to_c()), ctypes.byref(out)),
+           "lukv_decode_workspace_bytes")
+    return out.value
+
+
+def lukv_decode_attention(cfg: Config, q_dec, k_packed, v_packed, offsets, out, ws, stream=None) -> None:
+    _check(load_library().lukv_decode_attention(ctypes.byref(cfg.to_c()), _ptr(q_dec), _ptr(k_packed),
+                                                _ptr(v_packed), _ptr(offsets), _ptr(out), _ptr(ws),
+                                                ws.numel(), _stream(stream)), "lukv_decode_attention")
 
 
 def lukv_set_stage_events(events) -> None:

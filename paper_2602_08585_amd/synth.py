@@ -178,6 +178,19 @@ def make_layer_qkv(wl: Workload, layer: int) -> Dict[str, np.ndarray]:
             "v": _store(v_all, wl.dtype)}
 
 
+def make_decode_queries(wl: Workload, layers: Optional[List[int]] = None) -> np.ndarray:
+    """One decode query per (layer, query head, sequence): entries ~ N(0,1) * q_gain / sqrt(d),
+    rounded to the storage dtype; [NL, H_q, n_seqs, d] (the consumer test of the packed cache)."""
+    layers = list(range(wl.n_layers)) if layers is None else layers
+    d = wl.head_dim
+    out = np.empty((len(layers), wl.n_q_heads, wl.n_seqs, d), dtype=np.float32)
+    for li, layer in enumerate(layers):
+        rng = _rng(wl.seed, 4242, layer)
+        out[li] = rng.standard_normal((wl.n_q_heads, wl.n_seqs, d), dtype=np.float32) * \
+            np.float32(wl.q_gain / math.sqrt(d))
+    return _store(out, wl.dtype)
+
+
 def make_qkv(wl: Workload, layers: Optional[List[int]] = None) -> Dict[str, np.ndarray]:
     """Stack `make_layer_qkv` over layers: q_win [NL, H_q, n_seqs*w, d],
     k, v [NL, H_kv, total_len, d]."""

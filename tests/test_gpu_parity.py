@@ -593,3 +593,59 @@ def test_strided_inputs_and_custom_scale():
     ref = O.evict(p.data["q_win"], p.data["k"], p.data["v"], wl.cu_seqlens, wl.n_kv_heads, wl.window,
                   wl.pool_kernel, wl.n_sink, a["curves"], a["knots"], a["b_min"], a["b_max"], a["B"], scale=scale)
     assert _check_evict(p, out, ref) == 0
+
+
+@pytest.mark.parametrize("name", ["tiny", "bf16_g4_w32", "bf16_ragged", "bf16_g7_w16_d64", "f32_d128",
+                                  "bf16_mha_pool1_nosink", "bf16_g8_w64_rows512"])
+def test_decode_attention_over_the_packed_cache(name):
+    """Evict, then run one decode step's attention over the compacted cache (Eq. 3) and compare
+    with the oracle's attention over the rows the kept indices name."""
+    print("case", name, flush=True)
+    p = _problem(name)
+    wl = p.wl
+    G = wl.n_q_heads // wl.n_kv_heads
+    out = p.evict()
+    qd_h = synth.make_decode_queries(wl)
+    qd = dev(qd_h)
+    res = torch.full((wl.n_layers, wl.n_q_heads, wl.n_seqs, wl.head_dim), float("nan"), dtype=torch.float32,
+                     device="cuda")
+    ws = lukv.alloc_workspace(lukv.lukv_decode_workspace_bytes(p.cfg))
+    lukv.lukv_decode_attention(p.cfg, qd, out["k_out"], out["v_out"], out["offsets"], res, ws)
+    torch.cuda.synchronize()
+    got = res.cpu().numpy()
+    kept, offs = out["kept_idx"].cpu().numpy(), out["offsets"].cpu().numpy()
+    cu = wl.cu_seqlens
+    worst = 0.0
+    for s in range(wl.n_seqs):
+        for l in range(wl.n_layers):
+            for c in range(wl.n_kv_heads):
+                hi = (s * wl.n_layers + l) * wl.n_kv_heads + c
+                idx = kept[offs[hi]:offs[hi + 1]]
+                kr = O.decode(p.data["k"][l, c, cu[s]:cu[s + 1]][idx])
+                vr = O.decode(p.data["v"][l, c, cu[s]:cu[s + 1]][idx])
+                want = O.decode_attention(O.decode(qd_h[l, c * G:(c + 1) * G, s, :]), kr, vr)
+                g = got[l, c * G:(c + 1) * G, s, :]
+                tol = 1e-3 * np.abs(want).max() + 1e-7
+                worst = max(worst, float(np.abs(g - want).max() / tol))
+                assert np.abs(g - want).max() <= tol, (s, l, c)
+    print("decode attention worst error / tolerance:", round(worst, 4))
+
+
+def test_decode_attention_full_size_layer():
+    """The 8B/32k layer's compacted cache (52428 rows, uneven heads): sampled heads."""
+    print("case decode 8b_32k", flush=True)
+    wl = synth.workload("8b_32k")
+    p = Problem(wl)
+    out = p.evict()
+    qd_h = synth.make_decode_queries(wl)
+    res = torch.zeros((1, wl.n_q_heads, 1, wl.head_dim), dtype=torch.float32, device="cuda")
+    ws = lukv.alloc_workspace(lukv.lukv_decode_workspace_bytes(p.cfg))
+    lukv.lukv_decode_attention(p.cfg, dev(qd_h), out["k_out"], out["v_out"], out["offsets"], res, ws)
+    torch.cuda.synchronize()
+    got = res.cpu().numpy()
+    kept, offs = out["kept_idx"].cpu().numpy(), out["offsets"].cpu().numpy()
+    for c in (0, 3, 7):
+        idx = kept[offs[c]:offs[c + 1]]
+        want = O.decode_attention(O.decode(qd_h[0, c * 4:(c + 1) * 4, 0, :]), O.decode(p.data["k"][0, c][idx]),
+                                  O.decode(p.data["v"][0, c][idx]))
+        assert np.abs(got[0, c * 4:(c + 1) * 4, 0, :] - want).max() <= 1e-3 * np.abs(want).max() + 1e-7
