@@ -260,6 +260,27 @@ def test_allocate_parity_random_with_ties_and_bounds(seed):
         assert np.array_equal(g, w)
 
 
+@pytest.mark.parametrize("NH,Gp,L", [(1200, 6, 300), (40, 1980, 4000), (3, 2, 50)])
+def test_allocate_parity_beyond_the_workgroup_form(NH, Gp, L):
+    """More than 1024 heads, or more vertex-mask words than the 1024-thread form stages: the
+    general form of the budget phase (and the smallest legal grid)."""
+    print("case", NH, Gp, L, flush=True)
+    rng = np.random.default_rng(NH * 7 + Gp)
+    z = rng.standard_normal((1, NH, Gp))
+    inc = (0.5 * z * z).astype(np.float32)
+    inc[..., 0] = 0
+    curves = np.cumsum(inc, axis=-1).astype(np.float32)
+    knots = np.tile(synth.make_knots(L, Gp), (1, NH, 1))
+    b_min = rng.integers(0, max(1, L // 10), size=(1, NH)).astype(np.int32)
+    b_max = np.full((1, NH), L, np.int32)
+    B = np.array([int(b_min.sum()) + int(0.3 * (b_max.sum() - b_min.sum()))], np.int64)
+    got = _run_allocate(curves, knots, b_min, b_max, B)
+    want = _oracle_allocate(curves, knots, b_min, b_max, B)
+    for g, w in zip(got, want):
+        assert np.array_equal(g, w)
+    assert int(got[0].sum()) == int(B[0])
+
+
 # ---- selection edge cases -----------------------------------------------------------------
 
 def test_select_budget_extremes_and_clamp():
