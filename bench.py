@@ -162,39 +162,41 @@ def main() -> int:
     assert int(status.abs().sum()) == 0
     gc.enable()
 
-    # ---- per-stage durations: HIP events recorded by the library on the launch stream ------
+    # ---- per-kernel durations: the library attaches the caller's start / stop events to the
+    # dispatch of every stage's kernel (on the launch stream), so an elapsed time is the kernel's
+    # own duration, as a profiler reports it ------------------------------------------------------
     hip = _hip()
     hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
     hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
     hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
     n_ev = lukv.LUKV_NUM_STAGE_EVENTS
+    names = [lukv.lukv_stage_name(j) for j in range(lukv.LUKV_NUM_STAGES)]
+    used = [names.index(n) for n in ("score_stats", "score_accum", "sel_hist", "sel_tail", "sel_emit")]
     n_timed = min(args.steps, 64)
     ev_sets = []
     for _ in range(n_timed):
         arr = (ctypes.c_void_p * n_ev)()
-        for j in range(n_ev):
-            e = ctypes.c_void_p()
-            assert hip.hipEventCreate(ctypes.byref(e)) == 0
-            arr[j] = e
+        for st_i in used:
+            for j in (2 * st_i, 2 * st_i + 1):
+                e = ctypes.c_void_p()
+                assert hip.hipEventCreate(ctypes.byref(e)) == 0
+                arr[j] = e
         ev_sets.append(arr)
     for i in range(n_timed):
         lukv.lukv_set_stage_events(ev_sets[i])
         step(i)
     lukv.lukv_set_stage_events(None)
     torch.cuda.synchronize()
-    # lukv_evict records these stages (the allocation rides inside the two score kernels)
-    names = [lukv.lukv_stage_name(j) for j in range(n_ev)]
-    used = [names.index(n) for n in ("score_stats", "score_accum", "sel_hist", "sel_tail", "sel_emit", "end")]
-    stage_ms = np.zeros(len(used) - 1)
+    stage_ms = np.zeros(len(used))
     for arr in ev_sets:
-        for i, (a, b) in enumerate(zip(used[:-1], used[1:])):
+        for i, st_i in enumerate(used):
             ms = ctypes.c_float()
-            assert hip.hipEventElapsedTime(ctypes.byref(ms), arr[a], arr[b]) == 0
+            assert hip.hipEventElapsedTime(ctypes.byref(ms), arr[2 * st_i], arr[2 * st_i + 1]) == 0
             stage_ms[i] += ms.value
-        for j in range(n_ev):
-            hip.hipEventDestroy(arr[j])
+            hip.hipEventDestroy(arr[2 * st_i])
+            hip.hipEventDestroy(arr[2 * st_i + 1])
     stage_ms /= n_timed
-    stages = {names[a]: round(float(stage_ms[i]) * 1e3, 2) for i, a in enumerate(used[:-1])}
+    stages = {names[st_i]: round(float(stage_ms[i]) * 1e3, 2) for i, st_i in enumerate(used)}
 
     # algorithmic bytes per launch of the two streaming score kernels (8B/32k layer)
     esz = 2

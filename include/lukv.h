@@ -212,14 +212,15 @@ int lukv_decode_attention(const lukv_config* cfg, const void* q_dec, const void*
                           int64_t ws_bytes, void* stream);
 
 /* Instrumentation for benchmarks (process-wide, not thread-safe; for callers that time the path,
- * not part of the method).  While n_events > 0, every call records events[i] (hipEvent_t, created
- * by the caller, passed as void*) on its stream immediately before stage i, and lukv_evict records
- * events[LUKV_STAGE_END] after its last stage; entries that are NULL or beyond n_events are
- * skipped.  The array must stay valid until lukv_set_stage_events(NULL, 0).  Stage order:
- * allocate (stand-alone call only), score_stats, score_accum, pool (lukv_score only), sel_hist,
- * sel_tail, sel_emit, end (lukv_stage_name gives the same names; "" when out of range). */
-#define LUKV_STAGE_END 7
-#define LUKV_NUM_STAGE_EVENTS 8
+ * not part of the method).  While events are set, the main kernel of stage i of every call is
+ * launched with events[2*i] as its start event and events[2*i+1] as its stop event (hipEvent_t,
+ * created by the caller, passed as void*): hipEventElapsedTime(start, stop) is then that kernel's
+ * own duration, as a profiler reports it.  Entries that are NULL or beyond n_events are skipped.
+ * The array must stay valid until lukv_set_stage_events(NULL, 0).  Stages: allocate (the budget
+ * kernel of a stand-alone lukv_allocate), score_stats, score_accum, pool (lukv_score only),
+ * sel_hist, sel_tail, sel_emit (lukv_stage_name gives the same names; "" when out of range). */
+#define LUKV_NUM_STAGES 7
+#define LUKV_NUM_STAGE_EVENTS (2 * LUKV_NUM_STAGES)
 int lukv_set_stage_events(void* const* events, int32_t n_events);
 const char* lukv_stage_name(int32_t stage);
 

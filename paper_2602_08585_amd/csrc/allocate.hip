@@ -107,10 +107,9 @@ AllocIO make_alloc_io(int32_t n_problems, int32_t n_heads, int32_t n_grid, const
 }
 
 int launch_allocate(const AllocIO& io, hipStream_t st) {
-  stage_mark(kStAllocate, st);
   const int bpp = alloc_blocks_a(io.n_heads, io.n_grid);
   hipLaunchKernelGGL(allocate_vertices_kernel, dim3(io.n_problems * bpp), dim3(256), 0, st, io, bpp);
-  hipLaunchKernelGGL(allocate_budgets_kernel, dim3(io.n_problems), dim3(1024), 0, st, io);
+  launch_staged(kStAllocate, allocate_budgets_kernel, dim3(io.n_problems), dim3(1024), st, io);
   hipLaunchKernelGGL(offsets_kernel, dim3(1), dim3(256), 0, st, (const int32_t*)io.budgets, io.offsets,
                      (int64_t)io.n_problems * io.n_heads);
   return check_launch();

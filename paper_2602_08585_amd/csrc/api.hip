@@ -145,9 +145,11 @@ WsLayout make_layout(const HostCfg& hc, int32_t n_grid, bool alloc_only) {
 static void* const* g_stage_events = nullptr;
 static int g_n_stage_events = 0;
 
-void stage_mark(int stage, hipStream_t st) {
-  if (g_stage_events && stage < g_n_stage_events && g_stage_events[stage])
-    (void)hipEventRecord(static_cast<hipEvent_t>(g_stage_events[stage]), st);
+void stage_events(int stage, hipEvent_t* start, hipEvent_t* stop) {
+  *start = *stop = nullptr;
+  if (!g_stage_events) return;
+  if (2 * stage < g_n_stage_events) *start = static_cast<hipEvent_t>(g_stage_events[2 * stage]);
+  if (2 * stage + 1 < g_n_stage_events) *stop = static_cast<hipEvent_t>(g_stage_events[2 * stage + 1]);
 }
 
 static int check_ws(const WsLayout& lay, const void* ws, int64_t ws_bytes) {
@@ -288,7 +290,6 @@ static int evict_impl(const lukv_config* cfg, const void* q_win, const void* k, 
   if ((rc = launch_score_raw(hc, lay, q_win, k, lse, &aio, w, st))) return rc;
   rc = launch_select_compact(hc, lay, &aio, reinterpret_cast<const float*>(w + lay.raw), true, scores, budgets,
                              offsets, true, k, v, kept_idx, k_out, v_out, out_rows, sel_status, w, st);
-  stage_mark(kStEnd, st);
   return rc;
 }
 
@@ -398,7 +399,6 @@ int lukv_evict_budgets(const lukv_config* cfg, const void* q_win, const void* k,
   rc = launch_select_compact(hc, lay, nullptr, reinterpret_cast<const float*>(w + lay.raw), true, scores, budgets,
                              const_cast<int64_t*>(offsets), false, k, v, kept_idx, k_out, v_out, out_rows,
                              status, w, st);
-  stage_mark(kStEnd, st);
   return rc;
 }
 
@@ -434,9 +434,9 @@ int lukv_set_stage_events(void* const* events, int32_t n_events) {
 }
 
 const char* lukv_stage_name(int32_t stage) {
-  static const char* const names[kNumStageEvents] = {
-      "allocate", "score_stats", "score_accum", "pool", "sel_hist", "sel_tail", "sel_emit", "end"};
-  return stage >= 0 && stage < kNumStageEvents ? names[stage] : "";
+  static const char* const names[kNumStages] = {
+      "allocate", "score_stats", "score_accum", "pool", "sel_hist", "sel_tail", "sel_emit"};
+  return stage >= 0 && stage < kNumStages ? names[stage] : "";
 }
 
 const char* lukv_strerror(int code) {

@@ -2,6 +2,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include "lukv.h"
@@ -104,10 +105,21 @@ int64_t decode_workspace_bytes(const HostCfg& hc);
 int launch_decode(const HostCfg& hc, const void* q, const void* kp, const void* vp, const int64_t* offsets,
                   float* out, char* ws, hipStream_t st);
 
-// Optional instrumentation (lukv_set_stage_events): record the caller's event for a stage.
-enum Stage { kStAllocate = 0, kStStats, kStAccum, kStPool, kStHist, kStTail, kStEmit, kStEnd,
-             kNumStageEvents };
-void stage_mark(int stage, hipStream_t st);
+// Optional instrumentation (lukv_set_stage_events): the main kernel of a stage is launched with
+// the caller's start / stop events attached to its own dispatch.
+enum Stage { kStAllocate = 0, kStStats, kStAccum, kStPool, kStHist, kStTail, kStEmit, kNumStages };
+void stage_events(int stage, hipEvent_t* start, hipEvent_t* stop);   // NULLs when none are set
+
+template <class... KArgs, class... Args>
+inline void launch_staged(int stage, void (*kernel)(KArgs...), dim3 grid, dim3 block, hipStream_t st,
+                          Args... args) {
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  stage_events(stage, &e0, &e1);
+  if (e0 || e1)
+    hipExtLaunchKernelGGL(kernel, grid, block, 0, st, e0, e1, 0, static_cast<KArgs>(args)...);
+  else
+    hipLaunchKernelGGL(kernel, grid, block, 0, st, static_cast<KArgs>(args)...);
+}
 
 inline int check_launch() {
   return hipGetLastError() == hipSuccess ? LUKV_OK : LUKV_ELAUNCH;

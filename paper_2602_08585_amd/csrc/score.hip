@@ -512,15 +512,12 @@ static int launch_raw_t(const HostCfg& hc, const WsLayout& lay, const void* q, c
   if (aio) { io = *aio; bpp = alloc_blocks_a(aio->n_heads, aio->n_grid); n_alloc = (aio->n_problems * bpp + 7) / 8 * 8; }
   dim3 gridA(tabA.tile0[tabA.n_seqs], g.n_kv_heads, g.n_layers);
   dim3 gridB(tabB.tile0[tabB.n_seqs] + n_alloc, g.n_kv_heads, g.n_layers);
-  stage_mark(kStStats, st);
   if (!lse)
-    hipLaunchKernelGGL((score_stats_kernel<F32, D, NBM, RG>), gridA, dim3(256), 0, st, g, tabA,
-                       (const char*)q, (const char*)k, partial, lay.max_chunks,
-                       lay.rows_padded);
-  stage_mark(kStAccum, st);
-  hipLaunchKernelGGL((score_accum_kernel<F32, D, NBM, RG>), gridB, dim3(256), 0, st, g, tabB, io,
-                     n_alloc, bpp, (const char*)q, (const char*)k, (const float2*)partial, lse, raw,
-                     range, lay.max_chunks, lay.rows_padded);
+    launch_staged(kStStats, score_stats_kernel<F32, D, NBM, RG>, gridA, dim3(256), st, g, tabA,
+                  (const char*)q, (const char*)k, partial, lay.max_chunks, lay.rows_padded);
+  launch_staged(kStAccum, score_accum_kernel<F32, D, NBM, RG>, gridB, dim3(256), st, g, tabB, io,
+                n_alloc, bpp, (const char*)q, (const char*)k, (const float2*)partial, lse, raw,
+                range, lay.max_chunks, lay.rows_padded);
   return check_launch();
 }
 
@@ -549,9 +546,8 @@ int launch_pool(const HostCfg& hc, const WsLayout& lay, float* pooled_out, char*
   const Geom& g = hc.g;
   const SeqTab tabP = tiles_for(hc.seq, 256, 0);
   dim3 gridP(tabP.tile0[tabP.n_seqs], g.n_kv_heads * g.n_layers, 1);
-  stage_mark(kStPool, st);
-  hipLaunchKernelGGL(pool_kernel, gridP, dim3(256), 0, st, g, tabP,
-                     reinterpret_cast<const float*>(ws + lay.raw), pooled_out);
+  launch_staged(kStPool, pool_kernel, gridP, dim3(256), st, g, tabP,
+                reinterpret_cast<const float*>(ws + lay.raw), pooled_out);
   return check_launch();
 }
 

@@ -525,9 +525,9 @@ static void launch_emit(dim3 grid, hipStream_t st, SelGeom sg, const SeqTab& tab
                         const uint4* state, const uint2* slice_cnt, const int64_t* offsets,
                         const void* k, const void* v, const Geom& g, int esize, int32_t* kept_idx,
                         void* k_out, void* v_out, int64_t out_rows, int32_t* status) {
-  hipLaunchKernelGGL((sel_emit_kernel<ROW_BYTES>), grid, dim3(256), 0, st, sg, tab, pooled, state,
-                     slice_cnt, offsets, (const char*)k, (const char*)v, g.sl * esize, g.sh * esize,
-                     g.st * esize, kept_idx, (char*)k_out, (char*)v_out, out_rows, status);
+  launch_staged(kStEmit, sel_emit_kernel<ROW_BYTES>, grid, dim3(256), st, sg, tab, pooled, state,
+                slice_cnt, offsets, (const char*)k, (const char*)v, g.sl * esize, g.sh * esize,
+                g.st * esize, kept_idx, (char*)k_out, (char*)v_out, out_rows, status);
 }
 
 // scores_in: pooled scores (pool = false) or the unpooled metric (pool = true; the pooled
@@ -566,21 +566,18 @@ int launch_select_compact(const HostCfg& hc, const WsLayout& lay, const AllocIO*
   dim3 gridH(tabHW.tile0[tabHW.n_seqs] + n_alloc, g.n_kv_heads, g.n_layers);
   dim3 gridR(n_tiles, g.n_kv_heads, g.n_layers);
   dim3 gridE(tabE.tile0[tabE.n_seqs], g.n_kv_heads, g.n_layers);
-  stage_mark(kStHist, st);
   if (pool) {
-    hipLaunchKernelGGL(sel_hist_kernel<true>, gridH, dim3(1024), 0, st, sg, tabHW, io, n_alloc, scores_in,
-                       pooled_out, (const float2*)range, hist, by_bin, status);
+    launch_staged(kStHist, sel_hist_kernel<true>, gridH, dim3(1024), st, sg, tabHW, io, n_alloc, scores_in,
+                  pooled_out, (const float2*)range, hist, by_bin, status);
   } else {
     hipLaunchKernelGGL(sel_range_kernel, gridR, dim3(1024), 0, st, sg, tabH, scores_in, range);
-    hipLaunchKernelGGL(sel_hist_kernel<false>, gridH, dim3(1024), 0, st, sg, tabHW, io, n_alloc, scores_in,
-                       (float*)nullptr, (const float2*)range, hist, by_bin, status);
+    launch_staged(kStHist, sel_hist_kernel<false>, gridH, dim3(1024), st, sg, tabHW, io, n_alloc, scores_in,
+                  (float*)nullptr, (const float2*)range, hist, by_bin, status);
   }
   const float* sel_scores = pool ? pooled_out : scores_in;
-  stage_mark(kStTail, st);
-  hipLaunchKernelGGL(sel_tail_kernel, dim3(hc.n_hi), dim3(1024), 0, st, sg, tabH, budgets,
-                     (const unsigned*)hist, (const unsigned long long*)by_bin, state, slice_cnt, cand,
-                     make_offsets ? offsets : (int64_t*)nullptr, hc.n_hi, status);
-  stage_mark(kStEmit, st);
+  launch_staged(kStTail, sel_tail_kernel, dim3(hc.n_hi), dim3(1024), st, sg, tabH, budgets,
+                (const unsigned*)hist, (const unsigned long long*)by_bin, state, slice_cnt, cand,
+                make_offsets ? offsets : (int64_t*)nullptr, hc.n_hi, status);
   const int esize = g.f32 ? 4 : 2;
   const int row_bytes = g.head_dim * esize;
   if (row_bytes == 128)

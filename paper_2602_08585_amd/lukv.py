@@ -36,8 +36,8 @@ EXPORTS = ("lukv_workspace_bytes", "lukv_allocate_workspace_bytes", "lukv_score"
            "lukv_profile_workspace_bytes", "lukv_profile_build", "lukv_budgets_from_profile",
            "lukv_evict_budgets", "lukv_decode_workspace_bytes", "lukv_decode_attention",
            "lukv_set_stage_events", "lukv_stage_name", "lukv_strerror")
-LUKV_STAGE_END = 7
-LUKV_NUM_STAGE_EVENTS = 8
+LUKV_NUM_STAGES = 7
+LUKV_NUM_STAGE_EVENTS = 2 * LUKV_NUM_STAGES
 
 
 class _CConfig(ctypes.Structure):
