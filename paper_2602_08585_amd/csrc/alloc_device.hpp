@@ -16,9 +16,11 @@
 //            of workgroups.
 //   phase B: one workgroup per problem: a segment per vertex (to the next vertex), clipped to
 //            (b_min, min(b_max, last knot)], gain as an order-preserving 64-bit key; weighted
-//            radix select (8 digits of 8 bits) for g*; budgets per head, ties by a prefix
-//            sum over heads.  The row offsets (prefix sum of all budgets) are written by
-//            whoever consumes the budgets next.
+//            radix select for g* (by the whole workgroup, digits of up to 11 bits over the
+//            bits in which the keys differ, for up to 1024 heads; a general form on one wave
+//            with 8-bit digits beyond that); budgets per head, ties by a prefix sum over
+//            heads.  The row offsets (prefix sum of all budgets) are written by whoever
+//            consumes the budgets next.
 //
 // Nothing here may be fused: a gain is one fp64 subtract and one fp64 divide, so that it
 // compares bit for bit like the same expression evaluated on a CPU.

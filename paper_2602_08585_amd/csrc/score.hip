@@ -4,15 +4,17 @@
 //
 // Two streaming passes over K per (layer, sequence, KV head):
 //   stats  - S = K_tile * Q^T on the matrix cores; every lane owns one query row of a 32x32
-//            block and folds its 16 logits into a running (max, sum exp2) pair; the last
-//            workgroup of a head merges the per-chunk pairs into one constant per row,
-//            c_r = max_r * a + log2(sum_r), a = scale * log2(e).
-//   accum  - S = Q * K_tile^T, so that a lane owns one key column; P = exp2(S*a - c_r) is
-//            summed over the G*w rows in registers and written as the unpooled metric.
+//            block and folds its 16 logits into a running (max, sum exp2) pair; a workgroup
+//            leaves one pair per row for its chunk of keys.
+//   accum  - merges the head's per-chunk pairs into one constant per row, c_r = max_r * a +
+//            log2(sum_r), a = scale * log2(e) (or takes the caller's log-sum-exp); then
+//            S = Q * K_tile^T, so that a lane owns one key column; P = exp2(S*a - c_r) is
+//            summed over the G*w rows in registers and written as the unpooled metric,
+//            together with the (min, max) of what each wave wrote.
 // A third, tiny kernel applies the clipped max-pool and the +inf of forced positions when
 // the scores are wanted on their own (lukv_score); the fused path pools inside selection.
 //
-// A workgroup (4 waves) streams a chunk of keys in tiles of 128/RG keys: the next tile is
+// A workgroup (4 waves) streams a chunk of 512 to 2048 keys in tiles of 128/RG keys: the next tile is
 // in flight from HBM into registers while the current one, staged in LDS with a 16-byte row
 // pad (conflict-free 128-bit reads), feeds the matrix cores.  RG wave groups share the row
 // blocks when G*w > 32*NBM.
