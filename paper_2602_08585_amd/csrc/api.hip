@@ -132,6 +132,7 @@ WsLayout make_layout(const HostCfg& hc, int32_t n_grid, bool alloc_only) {
   w.sel_state = take(n_sel * 16);
   w.slice_cnt = take(n_sel * w.max_slices * 8);
   w.range = take(n_sel * w.range_stride * 8);
+  w.head_dig = take(n_sel * 8);
   w.by_bin = take(alloc_only ? 0 : score_bytes * 2);
   w.cand = take(alloc_only ? 0 : score_bytes * 2);
   const int64_t nseg = (int64_t)hc.n_hi * (n_grid > 0 ? n_grid : 0);

@@ -83,6 +83,7 @@ __global__ __launch_bounds__(256) void decode_partial_kernel(DecGeom g, const ch
 #pragma unroll
   for (int gq = 0; gq < kDecMaxGroup; ++gq) s[gq] = 0.f;
   if (t < R) {
+#pragma unroll 4
     for (int c = 0; c < kRowU4; ++c) {
       const u32x4 kv = tile[t * kLdsRowU4 + c];
       float kf[8];
@@ -147,15 +148,23 @@ __global__ __launch_bounds__(256) void decode_partial_kernel(DecGeom g, const ch
     const int gq = o / kWords, wd = o - gq * kWords;
     const float* pg = ps + gq * R;
     float a0 = 0.f, a1 = 0.f;
-    for (int r = 0; r < n; ++r) {
-      const unsigned w = tile32[r * (kLdsRowU4 * 4) + wd];
-      const float p = pg[r];
-      if constexpr (F32) {
-        a0 = fmaf(p, __uint_as_float(w), a0);
-      } else {
-        a0 = fmaf(p, __uint_as_float(w << 16), a0);
-        a1 = fmaf(p, __uint_as_float(w & 0xFFFF0000u), a1);
+    // rows beyond n carry p = 0 and a valid (clamped) row, so the loop runs over the whole
+    // block in steps of eight with the LDS reads of a step in flight together
+    for (int r0 = 0; r0 < R; r0 += 8) {
+      unsigned w[8];
+      float p[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) { w[u] = tile32[(r0 + u) * (kLdsRowU4 * 4) + wd]; p[u] = pg[r0 + u]; }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        if constexpr (F32) {
+          a0 = fmaf(p[u], __uint_as_float(w[u]), a0);
+        } else {
+          a0 = fmaf(p[u], __uint_as_float(w[u] << 16), a0);
+          a1 = fmaf(p[u], __uint_as_float(w[u] & 0xFFFF0000u), a1);
+        }
       }
+      if (r0 + 8 >= n) break;
     }
     my_part[gq * (D + 2) + wd * kCols] = a0;
     if constexpr (!F32) my_part[gq * (D + 2) + wd * kCols + 1] = a1;

@@ -49,6 +49,7 @@ struct WsLayout {
   int64_t alloc_vertex;          // i32 [n_problems * n_heads * n_grid]
   int64_t hist;                  // u32 [n_hi * max_slices * kHistBins / 2] packed 16-bit suffix counts
   int64_t range;                 // float2 [n_hi * range_stride] (min, max) of the metric per chunk part
+  int64_t head_dig;              // uint2 [n_hi] first digit of the selection: (base key, shift)
   int64_t by_bin;                // u64 [n_layers * n_kv_heads * total_tokens] (key, position) by slice and bin
   int64_t cand;                  // u64, same shape: threshold candidates of a head beyond the LDS list
   int64_t partial;               // float2 [n_hi * max_chunks * rows_padded]

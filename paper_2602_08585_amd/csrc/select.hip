@@ -99,7 +99,7 @@ template <bool POOL>
 __global__ __launch_bounds__(1024) void sel_hist_kernel(SelGeom sg, SeqTab tab, AllocIO aio,
                                                         int n_alloc_blocks, const float* src_scores,
                                                         float* pooled_out, const float2* range,
-                                                        unsigned* hist_parts,
+                                                        unsigned* hist_parts, uint2* head_dig,
                                                         unsigned long long* by_bin, int32_t* status) {
   __shared__ __align__(16) char scratch[kAllocLdsBytes];
   unsigned* lh = reinterpret_cast<unsigned*>(scratch);                      // kHistBins counters
@@ -152,6 +152,7 @@ __global__ __launch_bounds__(1024) void sel_hist_kernel(SelGeom sg, SeqTab tab, 
     lo = rng[0];
     shift = bits > 11 ? (unsigned)(bits - 11) : 0u;
   }
+  if (t == 0 && tile == 0) head_dig[hi] = make_uint2(lo, shift);   // the head's first digit, for sel_tail
   const int P = L - sg.window, h = sg.pool_kernel >> 1;
   const int n_slices = (L + kSliceElems - 1) / kSliceElems;
   // a workgroup takes sg.slices_per_wg consecutive slices (more than one in calls with
@@ -200,15 +201,19 @@ __global__ __launch_bounds__(1024) void sel_hist_kernel(SelGeom sg, SeqTab tab, 
 }
 
 // Exact threshold T among the n_c candidates of the list (the want-th largest, ties included)
-// by digits over the bits in which the candidates differ, and per-slice counts of candidates
+// by digits over the open bits of the bin's key interval, and per-slice counts of candidates
 // above and at T.  Entries are (key << 32) | position.  All threads call it.
 template <class List>
-__device__ __forceinline__ void tail_resolve(List list, unsigned n_c, unsigned want, unsigned* lh,
+__device__ __forceinline__ void tail_resolve(List list, unsigned n_c, unsigned want, bool interior,
+                                             unsigned bin_base, unsigned bin_bits, unsigned* lh,
                                              unsigned* part, unsigned* sel, unsigned* s_gt,
                                              unsigned* s_eq, unsigned& T_out, unsigned& r_eq_out) {
   const int t = threadIdx.x, lane = t & 63;
-  // bits in which the candidates vary
-  {
+  // The candidates lie in [base, base + 2^rest).  An interior bin is such an interval by
+  // construction; a clamped end bin is not, and its candidates' minimum and maximum are taken.
+  unsigned base = bin_base;
+  int rest = (int)bin_bits;
+  if (!interior) {
     unsigned cmin = 0xFFFFFFFFu, cmax = 0u;
     for (unsigned i = t; i < n_c; i += 1024) {
       const unsigned key = (unsigned)(list[i] >> 32);
@@ -224,38 +229,36 @@ __device__ __forceinline__ void tail_resolve(List list, unsigned n_c, unsigned w
       }
       if (lane == 0) { atomicMin(&sel[0], cmin); atomicMax(&sel[1], cmax); }
     }
+    __syncthreads();
+    base = sel[0];
+    const unsigned span = sel[1] - sel[0];
+    rest = span ? 32 - __clz(span) : 0;
   }
-  __syncthreads();
-  const unsigned cand_min = sel[0], vary = sel[0] ^ sel[1];
-  unsigned prefix = cand_min;        // all candidates equal: T is that key, `want` ties
-  if (vary != 0u) {
-    // digits of at most 11 bits from the top varying bit down; bits above it are common
-    int rest = 32 - __clz(vary);     // low bits still open
-    prefix = rest == 32 ? 0u : cand_min & ~((1u << rest) - 1u);
-    while (rest > 0) {
-      const int sh = rest > 11 ? rest - 11 : 0;
-      const unsigned mask = (1u << (rest - sh)) - 1u;
-      const unsigned hi_mask = rest == 32 ? 0u : ~((1u << rest) - 1u);
-      __syncthreads();
-      lh[t] = 0;
-      lh[t + 1024] = 0;
-      __syncthreads();
-      for (unsigned i = t; i < n_c; i += 1024) {
-        const unsigned key = (unsigned)(list[i] >> 32);
-        if ((key & hi_mask) == (prefix & hi_mask)) atomicAdd(&lh[(key >> sh) & mask], 1u);
-      }
-      __syncthreads();
-      const unsigned a1 = lh[2047 - 2 * t], a0 = lh[2046 - 2 * t];
-      const unsigned before = block_scan_u32(a1 + a0, part);
-      if (before < want && want <= before + a1) { sel[2] = 2047 - 2 * t; sel[3] = want - before; }
-      else if (before + a1 < want && want <= before + a1 + a0) { sel[2] = 2046 - 2 * t; sel[3] = want - before - a1; }
-      __syncthreads();
-      prefix |= sel[2] << sh;
-      want = sel[3];
-      rest = sh;
+  // digits of at most 11 bits of (key - base), from the top open bit down
+  unsigned prefix = 0u;
+  while (rest > 0) {
+    const int sh = rest > 11 ? rest - 11 : 0;
+    const unsigned mask = (1u << (rest - sh)) - 1u;
+    const unsigned hi_mask = rest == 32 ? 0u : ~((1u << rest) - 1u);
+    __syncthreads();
+    lh[t] = 0;
+    lh[t + 1024] = 0;
+    __syncthreads();
+    for (unsigned i = t; i < n_c; i += 1024) {
+      const unsigned dk = (unsigned)(list[i] >> 32) - base;
+      if ((dk & hi_mask) == (prefix & hi_mask)) atomicAdd(&lh[(dk >> sh) & mask], 1u);
     }
+    __syncthreads();
+    const unsigned a1 = lh[2047 - 2 * t], a0 = lh[2046 - 2 * t];
+    const unsigned before = block_scan_u32(a1 + a0, part);
+    if (before < want && want <= before + a1) { sel[2] = 2047 - 2 * t; sel[3] = want - before; }
+    else if (before + a1 < want && want <= before + a1 + a0) { sel[2] = 2046 - 2 * t; sel[3] = want - before - a1; }
+    __syncthreads();
+    prefix |= sel[2] << sh;
+    want = sel[3];
+    rest = sh;
   }
-  const unsigned T = prefix;
+  const unsigned T = base + prefix;
   for (unsigned i = t; i < n_c; i += 1024) {
     const unsigned long long e = list[i];
     const unsigned key = (unsigned)(e >> 32), sl = ((unsigned)e) >> 10;
@@ -286,7 +289,8 @@ __device__ __forceinline__ void tail_collect(List list, const unsigned long long
 // the budgets before it.
 __global__ __launch_bounds__(1024) void sel_tail_kernel(SelGeom sg, SeqTab tab, const int32_t* budgets,
                                                         const unsigned* hist_parts,
-                                                        const unsigned long long* by_bin, uint4* state,
+                                                        const unsigned long long* by_bin,
+                                                        const uint2* head_dig, uint4* state,
                                                         uint2* slice_cnt, unsigned long long* cand_glob,
                                                         int64_t* offsets_out, int n_heads_total,
                                                         int32_t* status) {
@@ -312,6 +316,7 @@ __global__ __launch_bounds__(1024) void sel_tail_kernel(SelGeom sg, SeqTab tab, 
 #pragma unroll
   for (int u = 0; u < 32; ++u) w[u] = u < n_slices ? hp[(int64_t)u * (kHistBins / 2)] : 0u;
   int kb = budgets[hi];
+  const uint2 dig = head_dig[hi];
   long long acc = 0;
   if (offsets_out)
     for (int h2 = t; h2 < hi; h2 += 1024) acc += budgets[h2];
@@ -389,16 +394,19 @@ __global__ __launch_bounds__(1024) void sel_tail_kernel(SelGeom sg, SeqTab tab, 
     c_off[t] = o;
   }
   __syncthreads();
+  // key interval of bin T0 (the two end bins are clamped and have none)
+  const bool interior = T0 > 0u && T0 < (unsigned)(kHistBins - 1);
+  const unsigned bin_base = dig.x + (T0 << dig.y);
   unsigned T, r_eq;
   if (n_cand <= (unsigned)kCandLds) {
     tail_collect(cand_lds, by_bin + head_base, n_slices, s_gt, c_cnt, c_off);
     __syncthreads();
-    tail_resolve(cand_lds, n_cand, want0, lh, part, sel, s_gt, s_eq, T, r_eq);
+    tail_resolve(cand_lds, n_cand, want0, interior, bin_base, dig.y, lh, part, sel, s_gt, s_eq, T, r_eq);
   } else {
     unsigned long long* list = cand_glob + head_base;
     tail_collect(list, by_bin + head_base, n_slices, s_gt, c_cnt, c_off);
     __syncthreads();
-    tail_resolve(list, n_cand, want0, lh, part, sel, s_gt, s_eq, T, r_eq);
+    tail_resolve(list, n_cand, want0, interior, bin_base, dig.y, lh, part, sel, s_gt, s_eq, T, r_eq);
   }
   __syncthreads();
   // nothing kept: a threshold above every key and no ties
@@ -554,6 +562,7 @@ int launch_select_compact(const HostCfg& hc, const WsLayout& lay, const AllocIO*
   const SeqTab tabHW = tiles_for(hc.seq, kSliceElems * sg.slices_per_wg, 0);
   unsigned* hist = reinterpret_cast<unsigned*>(ws + lay.hist);
   float2* range = reinterpret_cast<float2*>(ws + lay.range);
+  uint2* head_dig = reinterpret_cast<uint2*>(ws + lay.head_dig);
   uint4* state = reinterpret_cast<uint4*>(ws + lay.sel_state);
   uint2* slice_cnt = reinterpret_cast<uint2*>(ws + lay.slice_cnt);
   unsigned long long* by_bin = reinterpret_cast<unsigned long long*>(ws + lay.by_bin);
@@ -568,15 +577,15 @@ int launch_select_compact(const HostCfg& hc, const WsLayout& lay, const AllocIO*
   dim3 gridE(tabE.tile0[tabE.n_seqs], g.n_kv_heads, g.n_layers);
   if (pool) {
     launch_staged(kStHist, sel_hist_kernel<true>, gridH, dim3(1024), st, sg, tabHW, io, n_alloc, scores_in,
-                  pooled_out, (const float2*)range, hist, by_bin, status);
+                  pooled_out, (const float2*)range, hist, head_dig, by_bin, status);
   } else {
     hipLaunchKernelGGL(sel_range_kernel, gridR, dim3(1024), 0, st, sg, tabH, scores_in, range);
     launch_staged(kStHist, sel_hist_kernel<false>, gridH, dim3(1024), st, sg, tabHW, io, n_alloc, scores_in,
-                  (float*)nullptr, (const float2*)range, hist, by_bin, status);
+                  (float*)nullptr, (const float2*)range, hist, head_dig, by_bin, status);
   }
   const float* sel_scores = pool ? pooled_out : scores_in;
   launch_staged(kStTail, sel_tail_kernel, dim3(hc.n_hi), dim3(1024), st, sg, tabH, budgets,
-                (const unsigned*)hist, (const unsigned long long*)by_bin, state, slice_cnt, cand,
+                (const unsigned*)hist, (const unsigned long long*)by_bin, (const uint2*)head_dig, state, slice_cnt, cand,
                 make_offsets ? offsets : (int64_t*)nullptr, hc.n_hi, status);
   const int esize = g.f32 ? 4 : 2;
   const int row_bytes = g.head_dim * esize;
