@@ -78,32 +78,45 @@ __global__ __launch_bounds__(256) void decode_partial_kernel(DecGeom g, const ch
   }
   __syncthreads();
 
-  // logits of this thread's row (R = 128 rows: the first two waves)
+  // logits: two threads per row (R = 128 rows), each over half of the row's 16-byte pieces;
+  // the upper half's sums pass through LDS
+  static_assert(R == 128, "two threads per row");
+  const int row = t & (R - 1), half = t >> 7;
   float s[kDecMaxGroup];
 #pragma unroll
   for (int gq = 0; gq < kDecMaxGroup; ++gq) s[gq] = 0.f;
-  if (t < R) {
 #pragma unroll 4
-    for (int c = 0; c < kRowU4; ++c) {
-      const u32x4 kv = tile[t * kLdsRowU4 + c];
-      float kf[8];
-      if constexpr (F32) {
+  for (int c = half * (kRowU4 / 2); c < (half + 1) * (kRowU4 / 2); ++c) {
+    const u32x4 kv = tile[row * kLdsRowU4 + c];
+    float kf[8];
+    if constexpr (F32) {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) kf[e] = __uint_as_float(kv[e]);
-      } else {
-        unpack8<false>(kv, kf);
-      }
+      for (int e = 0; e < 4; ++e) kf[e] = __uint_as_float(kv[e]);
+    } else {
+      unpack8<false>(kv, kf);
+    }
 #pragma unroll
-      for (int gq = 0; gq < kDecMaxGroup; ++gq) {
-        if (gq < G) {
-          const float* qv = qs + gq * D + c * kPerU4;
+    for (int gq = 0; gq < kDecMaxGroup; ++gq) {
+      if (gq < G) {
+        const float* qv = qs + gq * D + c * kPerU4;
 #pragma unroll
-          for (int e = 0; e < kPerU4; ++e) s[gq] = fmaf(qv[e], kf[e], s[gq]);
-        }
+        for (int e = 0; e < kPerU4; ++e) s[gq] = fmaf(qv[e], kf[e], s[gq]);
       }
     }
   }
-  const bool live = t < n;
+  if (half) {
+#pragma unroll
+    for (int gq = 0; gq < kDecMaxGroup; ++gq)
+      if (gq < G) ps[gq * R + row] = s[gq];
+  }
+  __syncthreads();
+  if (!half) {
+#pragma unroll
+    for (int gq = 0; gq < kDecMaxGroup; ++gq)
+      if (gq < G) s[gq] += ps[gq * R + row];
+  }
+  __syncthreads();   // ps is rewritten with the probabilities below
+  const bool live = !half && row < n;
   // block maximum and sum of exponentials per query head
 #pragma unroll
   for (int gq = 0; gq < kDecMaxGroup; ++gq) {
