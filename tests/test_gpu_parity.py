@@ -670,3 +670,20 @@ def test_decode_attention_full_size_layer():
         want = O.decode_attention(O.decode(qd_h[0, c * 4:(c + 1) * 4, 0, :]), O.decode(p.data["k"][0, c][idx]),
                                   O.decode(p.data["v"][0, c][idx]))
         assert np.abs(got[0, c * 4:(c + 1) * 4, 0, :] - want).max() <= 1e-3 * np.abs(want).max() + 1e-7
+
+
+@pytest.mark.timeout(600)
+def test_evict_longest_sequence_the_library_takes():
+    """L = 1 048 576 tokens in one head (the documented limit): 64 chunks of 16384 keys, 1024
+    selection slices per head, thousands of row blocks in the gather."""
+    print("case L = 2^20", flush=True)
+    wl = synth.Workload(name="max_len", n_layers=1, n_q_heads=2, n_kv_heads=1, head_dim=64,
+                        seq_lens=[1 << 20], window=16, pool_kernel=7, n_sink=4, dtype=synth.BF16,
+                        keep_ratio=0.03, n_grid=32, heavy_frac=0.001, seed=77, q_gain=64.0)
+    p = Problem(wl)
+    out = p.evict()
+    n_band = _check_sampled_heads(p, out, [(0, 0, 0)], band=1e-3)
+    print("L = 2^20 band-only index differences:", n_band)
+    # one token more is refused on the host
+    with pytest.raises(lukv.LukvError):
+        lukv.lukv_workspace_bytes(dataclasses.replace(p.cfg, cu_seqlens=[0, (1 << 20) + 1]), wl.n_grid)
