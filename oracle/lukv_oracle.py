@@ -234,6 +234,17 @@ def offsets_of(budgets: np.ndarray) -> np.ndarray:
 # offline profile and online look-up (Sec. 4.3, Eq. 11; "Online Execution" steps 1-2)
 # ----------------------------------------------------------------------------
 
+def utility_curve(importance: np.ndarray, scores: np.ndarray, knots: Sequence[int]) -> np.ndarray:
+    """Profiled utility of one head on a grid of budgets (Sec. 4.1, Eq. 6 read as R-A1): the
+    tokens are ranked by the heuristic metric (descending score, ties to the lowest index, the
+    order M^pi takes them in) and U(i) = L(0) - L(M^pi(i)) is the importance mass of the first
+    i tokens of that ranking.  importance [T] >= 0, scores [T]; returns U at the knots, float32
+    (fp64 running sum in ranking order, rounded once)."""
+    order = np.argsort(-np.asarray(scores, dtype=np.float64), kind="stable")
+    u = np.concatenate([[0.0], np.cumsum(np.asarray(importance, dtype=np.float64)[order])])
+    return u[np.asarray(knots, dtype=np.int64)].astype(np.float32)
+
+
 def profile_build(curves: np.ndarray, knots: np.ndarray, b_min: np.ndarray, b_max: np.ndarray,
                   L: int, rho: Sequence[float]) -> np.ndarray:
     """Static profile Phi[n_rho, NH] (float32): for every calibration query m and every global

@@ -290,6 +290,28 @@ def test_profile_rows_reproduce_the_allocation_on_the_grid():
     assert np.all(np.diff(phi, axis=0) >= 0)        # compressing more never keeps more in a head
 
 
+def test_handworked_utility_curve_and_properties():
+    g = _golden()
+    imp = np.array([float(Fraction(t)) for t in g["curve_importance"]], np.float32)
+    sc = np.array([float(Fraction(t)) for t in g["curve_scores"]], np.float32)
+    assert O.utility_curve(imp, sc, range(5)).tolist() == [float(t) for t in g["curve_full"]]
+    assert O.utility_curve(imp, sc, [0, 2, 4]).tolist() == [float(t) for t in g["curve_knots_0_2_4"]]
+    rng = np.random.default_rng(31)
+    T = 200
+    imp = rng.random(T).astype(np.float32)
+    sc = rng.integers(0, 20, T).astype(np.float32)          # many ties
+    u = O.utility_curve(imp, sc, range(T + 1))
+    assert u[0] == 0 and np.all(np.diff(u) >= 0) and u[-1] == pytest.approx(float(imp.astype(np.float64).sum()), rel=1e-6)
+    # brute force: U(i) = importance of the i best tokens under (score desc, index asc)
+    rank = sorted(range(T), key=lambda j: (-float(sc[j]), j))
+    for i in (1, 7, 50, 199):
+        assert u[i] == pytest.approx(sum(float(imp[j]) for j in rank[:i]), rel=1e-6)
+    # ranking by the importance itself gives a concave curve (its own hull)
+    u2 = O.utility_curve(imp, imp, range(T + 1))
+    assert np.all(np.diff(u2, 2) <= 1e-6)
+    assert np.all(u2 >= u - 1e-5)
+
+
 # --- top-k and compaction -----------------------------------------------------------------
 
 @pytest.mark.parametrize("seed", range(5))

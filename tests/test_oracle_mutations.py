@@ -16,7 +16,7 @@ from tests import test_oracle_score as TS
 
 PUBLIC = ["window_attention_sum", "window_lse", "max_pool_1d", "score", "concave_hull", "marginal_gains",
           "_gain_of_unit", "_slope", "allocate", "select", "compact", "offsets_of", "profile_build",
-          "budgets_from_profile", "decode_attention"]
+          "budgets_from_profile", "decode_attention", "utility_curve"]
 
 MUTANTS = {
     # name: (snippet, replacement, pin that must fail)
@@ -64,6 +64,12 @@ MUTANTS = {
                              lambda: TS.test_decode_attention_library_cross_check()),
     "decode_values_for_keys": ("return p @ v_rows", "return p @ k_rows",
                                lambda: TS.test_decode_attention_handworked_and_special_cases()),
+    "curve_ranks_ascending": ('order = np.argsort(-np.asarray(scores, dtype=np.float64), kind="stable")\n    u =',
+                              'order = np.argsort(np.asarray(scores, dtype=np.float64), kind="stable")\n    u =',
+                              lambda: TA.test_handworked_utility_curve_and_properties()),
+    "curve_sums_unranked": ("np.cumsum(np.asarray(importance, dtype=np.float64)[order])",
+                            "np.cumsum(np.asarray(importance, dtype=np.float64))",
+                            lambda: TA.test_handworked_utility_curve_and_properties()),
     "sink_not_forced": ("s[:, :min(n_sink, L)] = np.inf", "pass",
                         lambda: TS.test_brute_force_definition()),
     "hull_keeps_collinear": ("if steepness_in > steepness_out:", "if steepness_in >= steepness_out:",
