@@ -176,6 +176,18 @@ int lukv_evict_lse(const lukv_config* cfg, const void* q_win, const void* k, con
  *   phi device [n_rho][n_heads]; b_min, b_max device int32 [n_heads]
  *   budgets device int32 [n_heads]; offsets device int64 [n_heads + 1]. */
 int lukv_profile_workspace_bytes(int32_t n_queries, int32_t n_heads, int32_t n_grid, int64_t* bytes);
+
+/* Offline profiling, first step (Sec. 4.1, Eq. 6): the utility curve of a head from per-token
+ * importance and the heuristic metric's ranking.  For each of n_curves (query, head) pairs the T
+ * tokens are ranked by (score descending, index ascending); U(i) is the importance of the first i
+ * tokens of the ranking (fp64 running sum); curves[c][g] = float(U(knots[c][g])).  The result is
+ * what lukv_profile_build and lukv_allocate take as `curves`.
+ *   importance, scores device float32 [n_curves][T] (importance >= 0, scores without NaN)
+ *   knots device int32 [n_curves][n_grid], values in [0, T] (others are clamped)
+ *   curves device float32 [n_curves][n_grid]
+ * Limits: 1 <= T <= 4096 (one profiled context is sorted in LDS), n_grid >= 1. */
+int lukv_profile_curves(int32_t n_curves, int32_t T, int32_t n_grid, const float* importance,
+                        const float* scores, const int32_t* knots, float* curves, void* stream);
 int lukv_profile_build(int32_t n_queries, int32_t n_heads, int32_t n_grid, const float* curves,
                        const int32_t* knots, const int32_t* b_min, const int32_t* b_max, int32_t L,
                        int32_t n_rho, const double* rho, float* phi, void* ws, int64_t ws_bytes,

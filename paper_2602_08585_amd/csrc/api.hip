@@ -338,6 +338,14 @@ int lukv_profile_workspace_bytes(int32_t n_queries, int32_t n_heads, int32_t n_g
   return LUKV_OK;
 }
 
+int lukv_profile_curves(int32_t n_curves, int32_t T, int32_t n_grid, const float* importance,
+                        const float* scores, const int32_t* knots, float* curves, void* stream) {
+  if (n_curves < 1 || T < 1 || T > 4096 || n_grid < 1 || !importance || !scores || !knots || !curves)
+    return LUKV_EINVAL;
+  return launch_profile_curves(n_curves, T, n_grid, importance, scores, knots, curves,
+                               static_cast<hipStream_t>(stream));
+}
+
 int lukv_profile_build(int32_t n_queries, int32_t n_heads, int32_t n_grid, const float* curves,
                        const int32_t* knots, const int32_t* b_min, const int32_t* b_max, int32_t L,
                        int32_t n_rho, const double* rho, float* phi, void* ws, int64_t ws_bytes,

@@ -101,6 +101,10 @@ int launch_profile_lookup(const float* row_lo, const float* row_hi, double t, in
                           const int32_t* b_min, const int32_t* b_max, int32_t* budgets, int64_t* offsets,
                           hipStream_t st);
 
+// utility curves from per-token importance (profile.hip)
+int launch_profile_curves(int32_t n_curves, int32_t T, int32_t n_grid, const float* importance,
+                          const float* scores, const int32_t* knots, float* curves, hipStream_t st);
+
 // decode-step attention over the packed cache (decode.hip)
 int64_t decode_workspace_bytes(const HostCfg& hc);
 int launch_decode(const HostCfg& hc, const void* q, const void* kp, const void* vp, const int64_t* offsets,

@@ -33,7 +33,7 @@ LUKV_ST_CLAMPED = 2
 
 EXPORTS = ("lukv_workspace_bytes", "lukv_allocate_workspace_bytes", "lukv_score", "lukv_allocate",
            "lukv_select_compact", "lukv_evict", "lukv_score_lse", "lukv_evict_lse",
-           "lukv_profile_workspace_bytes", "lukv_profile_build", "lukv_budgets_from_profile",
+           "lukv_profile_workspace_bytes", "lukv_profile_curves", "lukv_profile_build", "lukv_budgets_from_profile",
            "lukv_evict_budgets", "lukv_decode_workspace_bytes", "lukv_decode_attention",
            "lukv_set_stage_events", "lukv_stage_name", "lukv_strerror")
 LUKV_NUM_STAGES = 7
@@ -84,6 +84,7 @@ def load_library() -> ctypes.CDLL:
                                    P, P, P, P, P, P, P, P, I64, P]
     F64P = ctypes.POINTER(ctypes.c_double)
     lib.lukv_profile_workspace_bytes.argtypes = [I32, I32, I32, ctypes.POINTER(I64)]
+    lib.lukv_profile_curves.argtypes = [I32, I32, I32, P, P, P, P, P]
     lib.lukv_profile_build.argtypes = [I32, I32, I32, P, P, P, P, I32, I32, F64P, P, P, I64, P]
     lib.lukv_budgets_from_profile.argtypes = [I32, I32, F64P, P, ctypes.c_double, I32, P, P, P, P, P]
     lib.lukv_evict_budgets.argtypes = [CP, P, P, P, P, P, P, I64, P, P, P, P, P, P, I64, P]
@@ -269,6 +270,12 @@ def lukv_profile_workspace_bytes(n_queries: int, n_heads: int, n_grid: int) -> i
     _check(load_library().lukv_profile_workspace_bytes(n_queries, n_heads, n_grid, ctypes.byref(out)),
            "lukv_profile_workspace_bytes")
     return out.value
+
+
+def lukv_profile_curves(n_curves: int, T: int, n_grid: int, importance, scores, knots, curves,
+                        stream=None) -> None:
+    _check(load_library().lukv_profile_curves(n_curves, T, n_grid, _ptr(importance), _ptr(scores), _ptr(knots),
+                                              _ptr(curves), _stream(stream)), "lukv_profile_curves")
 
 
 def lukv_profile_build(n_queries: int, n_heads: int, n_grid: int, curves, knots, b_min, b_max, L: int,

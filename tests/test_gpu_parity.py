@@ -687,3 +687,34 @@ def test_evict_longest_sequence_the_library_takes():
     # one token more is refused on the host
     with pytest.raises(lukv.LukvError):
         lukv.lukv_workspace_bytes(dataclasses.replace(p.cfg, cu_seqlens=[0, (1 << 20) + 1]), wl.n_grid)
+
+
+@pytest.mark.parametrize("T,Gp", [(4096, 64), (1000, 17), (5, 3)])
+def test_profile_curves_from_importance(T, Gp):
+    """Utility curves from per-token importance and a score ranking with many ties (Eq. 6), then
+    the static profile built from them."""
+    print("case", T, Gp, flush=True)
+    rng = np.random.default_rng(T + Gp)
+    M, NH = 3, 6
+    imp = (rng.random((M * NH, T)) ** 4).astype(np.float32)
+    sc = (imp * rng.random((M * NH, T)) * 8).astype(np.float32).round(1)       # a noisy, quantised metric
+    sc[0, : T // 2] = 0.0                                                       # one curve: half the tokens tie
+    sc[1, ::3] = -0.0
+    knots = np.tile(synth.make_knots(T, Gp), (M * NH, 1)) if T >= Gp - 1 else np.tile(np.arange(Gp, dtype=np.int32) * T // (Gp - 1), (M * NH, 1))
+    want = np.stack([O.utility_curve(imp[c], sc[c], knots[c]) for c in range(M * NH)])
+    got = torch.full((M * NH, Gp), float("nan"), dtype=torch.float32, device="cuda")
+    lukv.lukv_profile_curves(M * NH, T, Gp, dev(imp), dev(sc), dev(knots), got)
+    torch.cuda.synchronize()
+    g = got.cpu().numpy()
+    assert np.allclose(g, want, rtol=1e-6, atol=0) and np.array_equal(g[:, 0], np.zeros(M * NH, np.float32))
+    # the curves feed the profile builder as they are
+    if T >= 64:
+        b_min = np.zeros((M, NH), np.int32)
+        b_max = np.full((M, NH), T, np.int32)
+        rho = [0.0, 0.5, 0.8, 0.95]
+        phi = torch.zeros((len(rho), NH), dtype=torch.float32, device="cuda")
+        ws = lukv.alloc_workspace(lukv.lukv_profile_workspace_bytes(M, NH, Gp))
+        lukv.lukv_profile_build(M, NH, Gp, got, dev(knots), dev(b_min), dev(b_max), T, rho, phi, ws)
+        torch.cuda.synchronize()
+        ref = O.profile_build(g.reshape(M, NH, Gp), knots.reshape(M, NH, Gp), b_min, b_max, T, rho)
+        assert np.array_equal(phi.cpu().numpy(), ref)
