@@ -157,20 +157,33 @@ __global__ __launch_bounds__(1024) void sel_hist_kernel(SelGeom sg, SeqTab tab, 
   const int n_slices = (L + kSliceElems - 1) / kSliceElems;
   // a workgroup takes sg.slices_per_wg consecutive slices (more than one in calls with
   // thousands of slices: fewer, longer workgroups)
-  for (int sl = tile * sg.slices_per_wg; sl < min(n_slices, (tile + 1) * sg.slices_per_wg); ++sl) {
+  // this thread's inputs of a slice: with POOL the raw metric at j0 - h + t and (for the halo)
+  // at j0 - h + 1024 + t, otherwise its own score; fetched one slice ahead
+  const int sl_end = min(n_slices, (tile + 1) * sg.slices_per_wg);
+  auto fetch = [&](int sl, float& a, float& b) {
+    const int j0 = sl * kSliceElems;
+    if (POOL) {
+      const int ja = j0 - h + t, jb = ja + 1024;
+      a = (ja >= 0 && ja < P) ? src[ja] : -INFINITY;
+      b = (t < 2 * h && jb < P) ? src[jb] : -INFINITY;
+    } else {
+      a = j0 + t < L ? src[j0 + t] : 0.f;
+      b = 0.f;
+    }
+  };
+  float in_a, in_b;
+  fetch(tile * sg.slices_per_wg, in_a, in_b);
+  for (int sl = tile * sg.slices_per_wg; sl < sl_end; ++sl) {
     unsigned* my_part = hist_parts + ((int64_t)hi * sg.max_slices + sl) * (kHistBins / 2);
     const int j0 = sl * kSliceElems, j = j0 + t;
     lh[t] = 0;
     lh[t + 1024] = 0;
-    float s = 0.f;
+    float s = in_a;
     if (POOL) {
-      for (int i = t; i < kSliceElems + 2 * h; i += 1024) {
-        const int jj = j0 - h + i;
-        rawt[i] = (jj >= 0 && jj < P) ? src[jj] : -INFINITY;
-      }
-    } else if (j < L) {
-      s = src[j];
+      rawt[t] = in_a;
+      if (t < 2 * h) rawt[1024 + t] = in_b;
     }
+    if (sl + 1 < sl_end) fetch(sl + 1, in_a, in_b);   // in flight during this slice's work
     __syncthreads();   // counters cleared, halo staged
     if (POOL && j < L) {
       // clipped max-pool over the prefix [0, P); window and sink positions are forced to +inf
