@@ -718,3 +718,31 @@ def test_profile_curves_from_importance(T, Gp):
         torch.cuda.synchronize()
         ref = O.profile_build(g.reshape(M, NH, Gp), knots.reshape(M, NH, Gp), b_min, b_max, T, rho)
         assert np.array_equal(phi.cpu().numpy(), ref)
+
+
+@pytest.mark.parametrize("name", ["bf16_ragged", "bf16_g5_w32"])
+def test_workspace_needs_no_initialisation(name):
+    """Whatever the workspace holds when a call starts (ones, random bytes, another call's
+    leftovers), the outputs are the same: every word is written before it is read."""
+    print("case", name, flush=True)
+    p = _problem(name)
+    ref = p.evict()
+    want = {k: v.clone() for k, v in ref.items()}
+    nbytes = p.ws.numel()
+    g = torch.Generator(device="cuda")
+    g.manual_seed(5)
+    for fill in ("ones", "random", "leftover"):
+        if fill == "ones":
+            p.ws.fill_(0xFF)
+        elif fill == "random":
+            p.ws.copy_(torch.randint(0, 256, (nbytes,), dtype=torch.uint8, device="cuda", generator=g))
+        else:
+            other = _problem("bf16_g4_w64")          # another shape leaves its scratch behind
+            big = lukv.alloc_workspace(max(nbytes, other.ws.numel()))
+            other.ws = big
+            other.evict()
+            p.ws = big
+        out = p.evict()
+        for key in ("budgets", "offsets", "kept_idx", "k_out", "v_out", "status"):
+            assert torch.equal(out[key], want[key]), (fill, key)
+        assert torch.equal(out["pooled"].view(torch.int32), want["pooled"].view(torch.int32)), fill
