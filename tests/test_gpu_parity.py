@@ -746,3 +746,41 @@ def test_workspace_needs_no_initialisation(name):
         for key in ("budgets", "offsets", "kept_idx", "k_out", "v_out", "status"):
             assert torch.equal(out[key], want[key]), (fill, key)
         assert torch.equal(out["pooled"].view(torch.int32), want["pooled"].view(torch.int32)), fill
+
+
+def test_evict_replays_from_a_hip_graph():
+    """A call only enqueues kernels (no memset nodes, no synchronisation, no allocation), so it
+    can be captured; every replay, with eager work and synchronisations in between, must equal
+    the eager result."""
+    print("case graph", flush=True)
+    p = _problem("bf16_ragged")
+    wl = p.wl
+    want = p.evict()
+    out = p.new_outputs()
+
+    def call():
+        lukv.lukv_evict(p.cfg, p.q, p.k, p.v, wl.n_grid, p.curves, p.knots, p.b_min, p.b_max, p.B,
+                        out["budgets"], out["offsets"], out["kept_idx"], out["k_out"], out["v_out"],
+                        out["pooled"], out["status"], p.ws)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        call()                                    # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        call()
+    for rep in range(4):
+        for key in ("budgets", "offsets", "kept_idx", "k_out", "v_out", "status", "pooled"):
+            out[key].fill_(0)
+        p.ws.fill_(rep)                            # scratch left in a different state each time
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        junk = p.evict()                           # eager work between the replays
+        for key in ("budgets", "offsets", "kept_idx", "k_out", "v_out", "status"):
+            assert torch.equal(out[key], want[key]), (rep, key)
+        assert torch.equal(out["pooled"].view(torch.int32), want["pooled"].view(torch.int32)), rep
+        del junk
