@@ -434,18 +434,49 @@ __global__ __launch_bounds__(256, (F32 && D == 128) ? 1 : 2) void score_accum_ke
       const u32x4* src = ktile + (32 * kt + (lane & 31)) * T::kLdsRowU4 + hf * T::kHalfU4;
 #pragma unroll
       for (int s = 0; s < T::kHalfU4; ++s) kreg[s] = src[s];
+      if (nb_count == NBM && !F32) {
+        // all row blocks live (wave-uniform): the softmax constants of every block are read
+        // first, then the matrix products of block nb+1 are issued one at a time between the
+        // exponentials of block nb (its 16 probabilities shared out over the MFMAs), so that the matrix pipe and
+        // the vector ALU of this wave run side by side
+        f32x16 acc = {0};
 #pragma unroll
-      for (int nb = 0; nb < NBM; ++nb) {
-        if (nb < nb_count) {
-          f32x16 acc = {0};
+        for (int s = 0; s < T::kHalfU4; ++s) acc = mma<F32>(qreg[0][s], kreg[s], acc);
 #pragma unroll
-          for (int s = 0; s < T::kHalfU4; ++s) acc = mma<F32>(qreg[nb][s], kreg[s], acc);
-          const float* rc = rowc_s + 32 * (blk0 + nb) + 4 * hf;
+        for (int nb = 0; nb < NBM; ++nb) {
+          f32x16 nxt = {0};
+          f32x4 cst[1][4];
 #pragma unroll
-          for (int v4 = 0; v4 < 4; ++v4) {
-            const f32x4 c4 = *reinterpret_cast<const f32x4*>(rc + 8 * v4);
+          for (int v4 = 0; v4 < 4; ++v4)
+            cst[0][v4] = *reinterpret_cast<const f32x4*>(rowc_s + 32 * (blk0 + nb) + 4 * hf + 8 * v4);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) col += fast_exp2(fmaf(acc[4 * v4 + e], a, -c4[e]));
+          for (int s = 0; s < T::kHalfU4; ++s) {
+            if (nb + 1 < NBM) nxt = mma<F32>(qreg[nb + 1][s], kreg[s], nxt);
+            // this step's share of the finished block's 16 elements
+            constexpr int kEl = 16 / T::kHalfU4;
+#pragma unroll
+            for (int e = s * kEl; e < (s + 1) * kEl; ++e) col += fast_exp2(fmaf(acc[e], a, -cst[0][e >> 2][e & 3]));
+            if (nb + 1 < NBM) {
+              __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);          // one MFMA
+              __builtin_amdgcn_sched_group_barrier(0x402, 3 * kEl, 0);    // kEl x (fma, exp2, add)
+            }
+          }
+          acc = nxt;
+        }
+      } else {
+#pragma unroll
+        for (int nb = 0; nb < NBM; ++nb) {
+          if (nb < nb_count) {
+            f32x16 acc = {0};
+#pragma unroll
+            for (int s = 0; s < T::kHalfU4; ++s) acc = mma<F32>(qreg[nb][s], kreg[s], acc);
+            const float* rc = rowc_s + 32 * (blk0 + nb) + 4 * hf;
+#pragma unroll
+            for (int v4 = 0; v4 < 4; ++v4) {
+              const f32x4 c4 = *reinterpret_cast<const f32x4*>(rc + 8 * v4);
+#pragma unroll
+              for (int e = 0; e < 4; ++e) col += fast_exp2(fmaf(acc[4 * v4 + e], a, -c4[e]));
+            }
           }
         }
       }
