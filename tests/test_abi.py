@@ -124,3 +124,21 @@ def test_bench_refuses_more_than_one_gpu():
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True,
                        text=True, timeout=120)
     assert r.returncode == 2 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_synthetic_inputs_are_seeded_and_bf16_rounding_is_nearest_even():
+    import numpy as np
+    import torch
+    wl = synth.workload("tiny")
+    a, b = synth.make_qkv(wl), synth.make_qkv(wl)
+    for key in ("q_win", "k", "v"):
+        assert np.array_equal(a[key], b[key])
+    c = synth.make_qkv(__import__("dataclasses").replace(wl, seed=wl.seed + 1))
+    assert not np.array_equal(a["k"], c["k"])
+    x = np.random.default_rng(0).standard_normal(4096).astype(np.float32)
+    x[:4] = [1.00390625, 1.01171875, -1.00390625, 3.0e38]          # exact ties (to even) and a large value
+    want = torch.from_numpy(x).to(torch.bfloat16).view(torch.uint16).numpy()
+    assert np.array_equal(synth.f32_to_bf16_bits(x), want)
+    al = synth.make_allocation_inputs(wl)
+    assert int(al["B"][0]) == 819 and al["curves"].shape == (1, 4, 32) and np.all(al["knots"][..., 0] == 0)
+    assert np.all(np.diff(al["knots"], axis=-1) > 0) and np.all(np.diff(al["curves"], axis=-1) >= 0)
