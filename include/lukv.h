@@ -7,6 +7,9 @@
  *   allocate global head-level budgets on the convex-hull relaxation    (Sec. 4.2, Eq. 8-10, App. A.2)
  *   select   per-head top-b_{l,h} positions by the metric               (Sec. 3.2 M^pi(k); Sec. 4.3 "Eviction")
  *   compact  the retained index sets as a dense per-head cache          (Sec. 3.2, Eq. 3)
+ * and, around it: the score with the window rows' log-sum-exp supplied (Sec. 4.3), the offline
+ * profile and its online look-up (Sec. 4.1 Eq. 6, Sec. 4.3 Eq. 11), and a decode step's
+ * attention over the compacted cache (Eq. 3).
  *
  * Conventions common to every call
  *   - "device" pointers are GPU memory owned by the caller (any allocator); "host" pointers are
