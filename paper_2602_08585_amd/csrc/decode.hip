@@ -117,15 +117,16 @@ __global__ __launch_bounds__(256) void decode_partial_kernel(DecGeom g, const ch
   }
   __syncthreads();   // ps is rewritten with the probabilities below
   const bool live = !half && row < n;
-  // block maximum and sum of exponentials per query head
+  // block maximum and sum of exponentials per query head (wave reductions on DPP steps)
+  auto fmax_bits = [](unsigned x, unsigned y) { return __float_as_uint(fmaxf(__uint_as_float(x), __uint_as_float(y))); };
+  auto fadd_bits = [](unsigned x, unsigned y) { return __float_as_uint(__uint_as_float(x) + __uint_as_float(y)); };
 #pragma unroll
   for (int gq = 0; gq < kDecMaxGroup; ++gq) {
     if (gq < G) {
       float m = live ? s[gq] * g.scale : -INFINITY;
       s[gq] = m;
-#pragma unroll
-      for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
-      if (lane == 0) red[wave][gq] = m;
+      m = __uint_as_float(wave_reduce_to_last(__float_as_uint(m), 0xFF800000u, fmax_bits));
+      if (lane == 63) red[wave][gq] = m;
     }
   }
   __syncthreads();
@@ -136,10 +137,8 @@ __global__ __launch_bounds__(256) void decode_partial_kernel(DecGeom g, const ch
     if (gq < G) {
       const float p = live ? __expf(s[gq] - stat[0][gq]) : 0.f;
       if (t < R) ps[gq * R + t] = p;
-      float l = p;
-#pragma unroll
-      for (int o = 32; o > 0; o >>= 1) l += __shfl_xor(l, o);
-      if (lane == 0) red[wave][gq] = l;
+      const float l = __uint_as_float(wave_reduce_to_last(__float_as_uint(p), 0u, fadd_bits));
+      if (lane == 63) red[wave][gq] = l;
     }
   }
   // the V tile takes the K tile's place (every thread is done reading K)
