@@ -190,11 +190,11 @@ __global__ __launch_bounds__(256) void decode_partial_kernel(DecGeom g, const ch
 // One workgroup per (query head of the group, head): the blocks' partial results are merged with
 // weights exp(m_b - M); D threads own the columns, 256 / D groups of them share the blocks.
 template <int D, int R>
-__global__ __launch_bounds__(256) void decode_combine_kernel(DecGeom g, const int64_t* offsets, const float* part,
-                                                             float* out) {
-  constexpr int NP = 256 / D;
-  __shared__ float red[4];
-  __shared__ float wts[256];
+__global__ __launch_bounds__(1024) void decode_combine_kernel(DecGeom g, const int64_t* offsets, const float* part,
+                                                              float* out) {
+  constexpr int NP = 1024 / D;          // groups of D threads that share the blocks
+  __shared__ float red[16];
+  __shared__ float wts[1024];
   __shared__ float accs[NP][D];
   const int gq = blockIdx.x, hi = blockIdx.y, t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int G = g.group;
@@ -210,15 +210,18 @@ __global__ __launch_bounds__(256) void decode_combine_kernel(DecGeom g, const in
     if (t < D) dst[t] = 0.f;
     return;
   }
+  auto fmax_bits = [](unsigned a, unsigned b) { return __float_as_uint(fmaxf(__uint_as_float(a), __uint_as_float(b))); };
+  auto fadd_bits = [](unsigned a, unsigned b) { return __float_as_uint(__uint_as_float(a) + __uint_as_float(b)); };
   float m = -INFINITY;
-  for (int b = t; b < n_blk; b += 256) m = fmaxf(m, hp[b * bstride + D]);
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
-  if (lane == 0) red[wave] = m;
+  for (int b = t; b < n_blk; b += 1024) m = fmaxf(m, hp[b * bstride + D]);
+  m = __uint_as_float(wave_reduce_to_last(__float_as_uint(m), 0xFF800000u, fmax_bits));
+  if (lane == 63) red[wave] = m;
   __syncthreads();
-  const float M = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+  float M = red[0];
+#pragma unroll
+  for (int w = 1; w < 16; ++w) M = fmaxf(M, red[w]);
   float l = 0.f, a = 0.f;
-  for (int b0 = 0; b0 < n_blk; b0 += 256) {
+  for (int b0 = 0; b0 < n_blk; b0 += 1024) {
     __syncthreads();
     float e = 0.f;
     if (b0 + t < n_blk) {
@@ -227,21 +230,22 @@ __global__ __launch_bounds__(256) void decode_combine_kernel(DecGeom g, const in
     }
     wts[t] = e;
     __syncthreads();
-    const int nb = n_blk - b0 < 256 ? n_blk - b0 : 256;
+    const int nb = n_blk - b0 < 1024 ? n_blk - b0 : 1024;
 #pragma unroll 4
     for (int bb = pt; bb < nb; bb += NP) a = fmaf(hp[(b0 + bb) * bstride + x], wts[bb], a);
   }
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) l += __shfl_xor(l, o);
+  l = __uint_as_float(wave_reduce_to_last(__float_as_uint(l), 0u, fadd_bits));
   __syncthreads();
-  if (lane == 0) red[wave] = l;
+  if (lane == 63) red[wave] = l;
   accs[pt][x] = a;
   __syncthreads();
   if (t < D) {
-    float tot = 0.f;
+    float tot = 0.f, den = 0.f;
 #pragma unroll
     for (int q2 = 0; q2 < NP; ++q2) tot += accs[q2][t];
-    dst[t] = tot / ((red[0] + red[1]) + (red[2] + red[3]));
+#pragma unroll
+    for (int w = 0; w < 16; ++w) den += red[w];
+    dst[t] = tot / den;
   }
 }
 
@@ -262,7 +266,7 @@ static int launch_decode_t(const HostCfg& hc, const void* q, const void* kp, con
   float* part = reinterpret_cast<float*>(ws);
   hipLaunchKernelGGL((decode_partial_kernel<F32, D, R>), dim3(dg.max_blocks, hc.n_hi), dim3(256), 0, st, dg,
                      (const char*)q, (const char*)kp, (const char*)vp, offsets, part);
-  hipLaunchKernelGGL((decode_combine_kernel<D, R>), dim3(g.group, hc.n_hi), dim3(256), 0, st, dg, offsets,
+  hipLaunchKernelGGL((decode_combine_kernel<D, R>), dim3(g.group, hc.n_hi), dim3(1024), 0, st, dg, offsets,
                      (const float*)part, out);
   return check_launch();
 }
