@@ -429,7 +429,7 @@ int lukv_decode_attention(const lukv_config* cfg, const void* q_dec, const void*
   if (rc) return rc;
   if (hc.g.group > 16) return LUKV_EINVAL;
   if (!q_dec || !k_packed || !v_packed || !offsets || !out) return LUKV_EINVAL;
-  if (!aligned16(k_packed) || !aligned16(v_packed)) return LUKV_EINVAL;
+  if (!aligned16(k_packed) || !aligned16(v_packed) || !aligned16(q_dec)) return LUKV_EINVAL;
   if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u) || ws_bytes < decode_workspace_bytes(hc))
     return LUKV_EWORKSPACE;
   return launch_decode(hc, q_dec, k_packed, v_packed, offsets, out, (char*)ws, static_cast<hipStream_t>(stream));

@@ -1,10 +1,10 @@
 // Consumer of the compacted cache: one decode step's attention over the retained entries of
 // every head (Sec. 3.2, Eq. 3 restricted to the index set I_{l,h}).  The packed K and V rows of
 // head hi sit at [offsets[hi], offsets[hi+1]); the G query heads of a group share them.
-//   decode_partial - one workgroup per (head, block of rows): K tile through LDS, one row per
-//                    thread for the G logits, block softmax statistics, then the V tile through
-//                    the same LDS buffer and p-weighted column sums; leaves (max, sum, weighted
-//                    values) per query head.
+//   decode_partial - one workgroup per (head, block of 128 rows): K tile through LDS, the G logits
+//                    of every row on the matrix cores (bf16; plain dot products for f32), block
+//                    softmax statistics, then the V tile through the same LDS buffer and
+//                    p-weighted column sums; leaves (max, sum, weighted values) per query head.
 //   decode_combine - one workgroup per (query head, head): merges the blocks' partial results.
 // Row counts live on the device (they are budgets), so the grid covers the longest possible
 // head and workgroups beyond a head's rows exit at once.
@@ -19,18 +19,6 @@ struct DecGeom {
   float scale;
 };
 
-template <bool F32>
-__device__ __forceinline__ void unpack8(const u32x4& v, float (&f)[8]);
-
-template <>
-__device__ __forceinline__ void unpack8<false>(const u32x4& v, float (&f)[8]) {
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    f[2 * i] = __uint_as_float(v[i] << 16);
-    f[2 * i + 1] = __uint_as_float(v[i] & 0xFFFF0000u);
-  }
-}
-
 // R rows per block; a row is D elements = kRowU4 16-byte pieces, padded by one piece in LDS.
 template <bool F32, int D, int R>
 __global__ __launch_bounds__(256) void decode_partial_kernel(DecGeom g, const char* q, const char* kp,
@@ -42,7 +30,7 @@ __global__ __launch_bounds__(256) void decode_partial_kernel(DecGeom g, const ch
   constexpr int kLoads = R * kRowU4 / 256;
   constexpr int kPerU4 = 16 / kEsize;            // elements in one 16-byte piece
   __shared__ u32x4 tile[R * kLdsRowU4];
-  __shared__ float qs[kDecMaxGroup * D];
+  __shared__ u32x4 qbuf[32 * kLdsRowU4];          // the group's queries: 32 padded rows (bf16) or floats
   __shared__ float ps[kDecMaxGroup * R];
   __shared__ float red[4][kDecMaxGroup];
   __shared__ float stat[2][kDecMaxGroup];
@@ -54,6 +42,7 @@ __global__ __launch_bounds__(256) void decode_partial_kernel(DecGeom g, const ch
   const int G = g.group;
   const int kvh = hi % g.n_kv_heads, layer = (hi / g.n_kv_heads) % g.n_layers;
   const int seq = hi / (g.n_kv_heads * g.n_layers);
+  static_assert(R == 128, "four waves of 32 rows / two threads per row");
 
   // K and V tiles: 16 bytes per lane, rows beyond the block clamped to its last row
   u32x4 kr[kLoads], vr[kLoads];
@@ -64,12 +53,21 @@ __global__ __launch_bounds__(256) void decode_partial_kernel(DecGeom g, const ch
     kr[u] = *reinterpret_cast<const u32x4*>(kp + (row * kRowU4 + c) * 16);
     vr[u] = *reinterpret_cast<const u32x4*>(vp + (row * kRowU4 + c) * 16);
   }
-  // the group's decode queries as floats
-  for (int i = t; i < G * D; i += 256) {
-    const int gq = i / D, x = i - gq * D;
-    const int64_t qi = (((int64_t)layer * g.n_q_heads + kvh * G + gq) * g.n_seqs + seq) * D + x;
-    qs[i] = F32 ? reinterpret_cast<const float*>(q)[qi]
-                : __uint_as_float((unsigned)reinterpret_cast<const unsigned short*>(q)[qi] << 16);
+  auto q_row = [&](int gq) {   // element index of query head gq's row
+    return (((int64_t)layer * g.n_q_heads + kvh * G + gq) * g.n_seqs + seq) * D;
+  };
+  float* qs = reinterpret_cast<float*>(qbuf);
+  if constexpr (F32) {
+    // the group's decode queries as floats
+    for (int i = t; i < G * D; i += 256) qs[i] = reinterpret_cast<const float*>(q)[q_row(i / D) + i % D];
+  } else {
+    // as a 32-row bf16 operand tile (rows beyond the group are zero)
+    for (int i = t; i < 32 * kRowU4; i += 256) {
+      const int r = i / kRowU4, c = i % kRowU4;
+      u32x4 v = {0u, 0u, 0u, 0u};
+      if (r < G) v = *reinterpret_cast<const u32x4*>(q + (q_row(r) + c * 8) * 2);
+      qbuf[r * kLdsRowU4 + c] = v;
+    }
   }
 #pragma unroll
   for (int u = 0; u < kLoads; ++u) {
@@ -78,67 +76,102 @@ __global__ __launch_bounds__(256) void decode_partial_kernel(DecGeom g, const ch
   }
   __syncthreads();
 
-  // logits: two threads per row (R = 128 rows), each over half of the row's 16-byte pieces;
-  // the upper half's sums pass through LDS
-  static_assert(R == 128, "two threads per row");
-  const int row = t & (R - 1), half = t >> 7;
-  float s[kDecMaxGroup];
+  auto fmax_bits = [](unsigned x, unsigned y) { return __float_as_uint(fmaxf(__uint_as_float(x), __uint_as_float(y))); };
+  auto fadd_bits = [](unsigned x, unsigned y) { return __float_as_uint(__uint_as_float(x) + __uint_as_float(y)); };
+  if constexpr (!F32) {
+    // logits on the matrix cores: wave w takes rows 32w .. 32w+31, S = K_rows * Q^T (32 x 32, the
+    // first G columns live).  Both operands: lane l supplies row l%32 and, of its half l/32 of
+    // the row, the 8 elements of step s.  acc[v] is row 8*(v/4) + 4*(l/32) + v%4, column l%32.
+    typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+    typedef __attribute__((ext_vector_type(16))) float f32x16;
+    const int hf = lane >> 5, gq = lane & 31;
+    f32x16 acc = {0};
 #pragma unroll
-  for (int gq = 0; gq < kDecMaxGroup; ++gq) s[gq] = 0.f;
+    for (int st = 0; st < kRowU4 / 2; ++st) {
+      const u32x4 av = tile[(32 * wave + gq) * kLdsRowU4 + hf * (kRowU4 / 2) + st];
+      const u32x4 bv = qbuf[gq * kLdsRowU4 + hf * (kRowU4 / 2) + st];
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), __builtin_bit_cast(bf16x8, bv),
+                                                    acc, 0, 0, 0);
+    }
+    float sv[16], m = -INFINITY;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int r = 32 * wave + 8 * (v >> 2) + 4 * hf + (v & 3);
+      sv[v] = r < n ? acc[v] * g.scale : -INFINITY;
+      m = fmaxf(m, sv[v]);
+    }
+    m = fmaxf(m, __shfl_xor(m, 32));                 // the two halves of the rows
+    if (lane < 32 && gq < G) red[wave][gq] = m;
+    __syncthreads();
+    if (t < G) stat[0][t] = fmaxf(fmaxf(red[0][t], red[1][t]), fmaxf(red[2][t], red[3][t]));
+    __syncthreads();
+    const float M = gq < G ? stat[0][gq] : 0.f;
+    float l = 0.f;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int r = 32 * wave + 8 * (v >> 2) + 4 * hf + (v & 3);
+      const float pv = r < n ? __expf(sv[v] - M) : 0.f;
+      if (gq < G) ps[gq * R + r] = pv;
+      l += pv;
+    }
+    l += __shfl_xor(l, 32);
+    if (lane < 32 && gq < G) red[wave][gq] = l;
+  } else {
+    // logits: two threads per row, each over half of the row's 16-byte pieces; the upper half's
+    // sums pass through LDS
+    const int row = t & (R - 1), half = t >> 7;
+    float s[kDecMaxGroup];
+#pragma unroll
+    for (int gq = 0; gq < kDecMaxGroup; ++gq) s[gq] = 0.f;
 #pragma unroll 4
-  for (int c = half * (kRowU4 / 2); c < (half + 1) * (kRowU4 / 2); ++c) {
-    const u32x4 kv = tile[row * kLdsRowU4 + c];
-    float kf[8];
-    if constexpr (F32) {
+    for (int c = half * (kRowU4 / 2); c < (half + 1) * (kRowU4 / 2); ++c) {
+      const u32x4 kv = tile[row * kLdsRowU4 + c];
+      float kf[4];
 #pragma unroll
       for (int e = 0; e < 4; ++e) kf[e] = __uint_as_float(kv[e]);
-    } else {
-      unpack8<false>(kv, kf);
+#pragma unroll
+      for (int gq = 0; gq < kDecMaxGroup; ++gq) {
+        if (gq < G) {
+          const float* qv = qs + gq * D + c * kPerU4;
+#pragma unroll
+          for (int e = 0; e < kPerU4; ++e) s[gq] = fmaf(qv[e], kf[e], s[gq]);
+        }
+      }
     }
+    if (half) {
+#pragma unroll
+      for (int gq = 0; gq < kDecMaxGroup; ++gq)
+        if (gq < G) ps[gq * R + row] = s[gq];
+    }
+    __syncthreads();
+    if (!half) {
+#pragma unroll
+      for (int gq = 0; gq < kDecMaxGroup; ++gq)
+        if (gq < G) s[gq] += ps[gq * R + row];
+    }
+    __syncthreads();   // ps is rewritten with the probabilities below
+    const bool live = !half && row < n;
+    // block maximum and sum of exponentials per query head (wave reductions on DPP steps)
 #pragma unroll
     for (int gq = 0; gq < kDecMaxGroup; ++gq) {
       if (gq < G) {
-        const float* qv = qs + gq * D + c * kPerU4;
-#pragma unroll
-        for (int e = 0; e < kPerU4; ++e) s[gq] = fmaf(qv[e], kf[e], s[gq]);
+        float m = live ? s[gq] * g.scale : -INFINITY;
+        s[gq] = m;
+        m = __uint_as_float(wave_reduce_to_last(__float_as_uint(m), 0xFF800000u, fmax_bits));
+        if (lane == 63) red[wave][gq] = m;
       }
     }
-  }
-  if (half) {
+    __syncthreads();
+    if (t < G) stat[0][t] = fmaxf(fmaxf(red[0][t], red[1][t]), fmaxf(red[2][t], red[3][t]));
+    __syncthreads();
 #pragma unroll
-    for (int gq = 0; gq < kDecMaxGroup; ++gq)
-      if (gq < G) ps[gq * R + row] = s[gq];
-  }
-  __syncthreads();
-  if (!half) {
-#pragma unroll
-    for (int gq = 0; gq < kDecMaxGroup; ++gq)
-      if (gq < G) s[gq] += ps[gq * R + row];
-  }
-  __syncthreads();   // ps is rewritten with the probabilities below
-  const bool live = !half && row < n;
-  // block maximum and sum of exponentials per query head (wave reductions on DPP steps)
-  auto fmax_bits = [](unsigned x, unsigned y) { return __float_as_uint(fmaxf(__uint_as_float(x), __uint_as_float(y))); };
-  auto fadd_bits = [](unsigned x, unsigned y) { return __float_as_uint(__uint_as_float(x) + __uint_as_float(y)); };
-#pragma unroll
-  for (int gq = 0; gq < kDecMaxGroup; ++gq) {
-    if (gq < G) {
-      float m = live ? s[gq] * g.scale : -INFINITY;
-      s[gq] = m;
-      m = __uint_as_float(wave_reduce_to_last(__float_as_uint(m), 0xFF800000u, fmax_bits));
-      if (lane == 63) red[wave][gq] = m;
-    }
-  }
-  __syncthreads();
-  if (t < G) stat[0][t] = fmaxf(fmaxf(red[0][t], red[1][t]), fmaxf(red[2][t], red[3][t]));
-  __syncthreads();
-#pragma unroll
-  for (int gq = 0; gq < kDecMaxGroup; ++gq) {
-    if (gq < G) {
-      const float p = live ? __expf(s[gq] - stat[0][gq]) : 0.f;
-      if (t < R) ps[gq * R + t] = p;
-      const float l = __uint_as_float(wave_reduce_to_last(__float_as_uint(p), 0u, fadd_bits));
-      if (lane == 63) red[wave][gq] = l;
+    for (int gq = 0; gq < kDecMaxGroup; ++gq) {
+      if (gq < G) {
+        const float p = live ? __expf(s[gq] - stat[0][gq]) : 0.f;
+        if (t < R) ps[gq * R + t] = p;
+        const float l = __uint_as_float(wave_reduce_to_last(__float_as_uint(p), 0u, fadd_bits));
+        if (lane == 63) red[wave][gq] = l;
+      }
     }
   }
   // the V tile takes the K tile's place (every thread is done reading K)
