@@ -784,3 +784,25 @@ def test_evict_replays_from_a_hip_graph():
             assert torch.equal(out[key], want[key]), (rep, key)
         assert torch.equal(out["pooled"].view(torch.int32), want["pooled"].view(torch.int32)), rep
         del junk
+
+
+def test_lse_variant_full_size_8b_32k():
+    """The configuration bench.py times as `lse_variant`: budgets bit-exact, sampled heads against
+    the oracle run with the same log-sum-exp."""
+    print("case 8b_32k with lse", flush=True)
+    wl = synth.workload("8b_32k")
+    p = Problem(wl)
+    lse_h = p.oracle_lse()
+    out = p.evict_lse(dev(lse_h))
+    a = p.alloc
+    budgets_ref = O.allocate(a["curves"][0], a["knots"][0], a["b_min"][0], a["b_max"][0], int(a["B"][0]))[0]
+    offs = O.offsets_of(budgets_ref)
+    assert np.array_equal(out["budgets"].cpu().numpy(), budgets_ref)
+    assert int(out["status"].abs().sum()) == 0
+    kept, pooled = out["kept_idx"].cpu().numpy(), out["pooled"].cpu().numpy()
+    G, w = wl.n_q_heads // wl.n_kv_heads, wl.window
+    for c in (2, 5):
+        S = O.score(O.decode(p.data["q_win"][0, c * G:(c + 1) * G]), O.decode(p.data["k"][0, c:c + 1]), 1, w,
+                    wl.pool_kernel, wl.n_sink, lse=lse_h[0, c * G:(c + 1) * G])[0]
+        assert_scores_close(pooled[0, c], S)
+        check_band(kept[offs[c]:offs[c + 1]], O.select(S, int(budgets_ref[c])), S, 1e-3)
