@@ -157,30 +157,24 @@ def concave_hull(knots: Sequence[int], U: Sequence[float]) -> List[int]:
     """Indices of the knots that are vertices of the upper concave hull of (knots[g], U[g]).
 
     The profiled utility U(i) = L(0) - L(i) is the retained importance mass; the
-    paper's convex non-increasing surrogate of the loss (PAVA on the marginal
-    decreases) is the least concave majorant of U.  Between grid knots U is taken
-    linear, so the hull of the knots is the hull of the curve.
+    paper's convex non-increasing surrogate of the loss is obtained by the
+    Pool-Adjacent-Violators scan over the marginal decreases (Sec. 4.2, App. A.2),
+    which is the least concave majorant of U.  Between grid knots U is taken linear,
+    so the hull of the knots is the hull of the curve.
 
-    Written as the definition of a strict vertex: knot g is on the hull iff every
-    chord from an earlier knot to g is strictly steeper than every chord from g to a
-    later knot (the two end knots always are).  Collinear knots are therefore not
-    vertices, and the slopes between consecutive vertices are strictly decreasing.
+    The scan, left to right over the grid intervals: every interval starts as a block
+    of its own whose gain is the mean marginal decrease over the block, i.e. the chord
+    between the block's end knots; while the newest block's gain is not strictly below
+    the gain of the block before it, the two are pooled into one block (whose gain is
+    again the chord between ITS end knots).  The blocks that remain have strictly
+    decreasing gains; their end knots are the hull vertices (collinear knots pool away).
     """
-    G = len(knots)
-    n = np.asarray(knots, dtype=np.int64).astype(np.float64)
-    u = np.asarray(U, dtype=np.float32).astype(np.float64)
-    with np.errstate(divide="ignore", invalid="ignore"):
-        chord = (u[None, :] - u[:, None]) / (n[None, :] - n[:, None])   # chord[a, b], a < b used
-    hull = []
-    for g in range(G):
-        if g == 0 or g == G - 1:
-            hull.append(g)
-            continue
-        steepness_in = chord[:g, g].min()          # chords from earlier knots to g
-        steepness_out = chord[g, g + 1:].max()     # chords from g to later knots
-        if steepness_in > steepness_out:
-            hull.append(g)
-    return hull
+    ends: List[int] = [0]                  # ends[i], ends[i+1] = end knots of block i
+    for g in range(1, len(knots)):
+        ends.append(g)
+        while len(ends) >= 3 and _slope(knots, U, ends[-3], ends[-2]) <= _slope(knots, U, ends[-2], ends[-1]):
+            del ends[-2]                   # pool the last two blocks
+    return ends
 
 
 def marginal_gains(knots: Sequence[int], U: Sequence[float]) -> List[Tuple[int, int, float]]:

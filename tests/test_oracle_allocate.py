@@ -62,19 +62,29 @@ def test_infeasible_budgets_flagged():
     assert st == 1 and b.tolist() == [3, 3]
 
 
-# --- monotone chain (textbook upper-hull scan) as a second construction of the same hull ---
+# --- the hull by the definition of a strict vertex: a second, order-free construction ---------
 
-def _monotone_chain(knots, U):
-    st = []
-    for g in range(len(knots)):
-        st.append(g)
-        while len(st) >= 3 and O._slope(knots, U, st[-3], st[-2]) <= O._slope(knots, U, st[-2], st[-1]):
-            del st[-2]
-    return st
+def _vertices_by_chords(knots, U):
+    """Knot g is a vertex of the upper concave hull iff every chord from an earlier knot to g is
+    strictly steeper than every chord from g to a later knot (the end knots always are).  Same
+    fp64 chord expression as the oracle's gain (one subtract, one divide), but no scan order."""
+    G = len(knots)
+    n = np.asarray(knots, dtype=np.int64).astype(np.float64)
+    u = np.asarray(U, dtype=np.float32).astype(np.float64)
+    out = []
+    for g in range(G):
+        if g == 0 or g == G - 1:
+            out.append(g)
+            continue
+        steep_in = min((u[g] - u[a]) / (n[g] - n[a]) for a in range(g))
+        steep_out = max((u[c] - u[g]) / (n[c] - n[g]) for c in range(g + 1, G))
+        if steep_in > steep_out:
+            out.append(g)
+    return out
 
 
 @pytest.mark.parametrize("seed", range(10))
-def test_vertex_definition_equals_monotone_chain(seed):
+def test_scan_equals_vertex_definition(seed):
     rng = np.random.default_rng(700 + seed)
     Gp = int(rng.integers(2, 40))
     L = int(rng.integers(Gp, 4000))
@@ -86,7 +96,43 @@ def test_vertex_definition_equals_monotone_chain(seed):
     inc[0] = 0
     U = np.cumsum(inc).astype(np.float32)
     knots = ((np.arange(Gp) * L) // (Gp - 1)).astype(np.int32) if Gp > 1 else np.zeros(1, np.int32)
-    assert O.concave_hull(knots, U) == _monotone_chain(knots, U)
+    assert O.concave_hull(knots, U) == _vertices_by_chords(knots, U)
+
+
+def _near_collinear_curve(rng):
+    """A curve whose knots lie on (or within a few float32 ulps of) one or two straight lines:
+    the case in which rounding of the fp64 chords could make two constructions disagree."""
+    Gp = int(rng.integers(3, 24))
+    top = int(rng.choice([Gp + 5, 300, 4096, 1 << 17, 1 << 20]))
+    knots = np.unique(np.concatenate([[0], rng.integers(1, top, size=Gp - 2), [top]])).astype(np.int64)
+    Gp = knots.size
+    kind = int(rng.integers(0, 4))
+    slope = float(rng.choice([1.0, 1 / 3, 0.1, 7.0, 1e-3])) * float(rng.uniform(0.5, 2.0))
+    exact = knots.astype(np.float64) * slope
+    if kind == 1:                                   # a second, slightly flatter line after a break
+        brk = int(rng.integers(1, Gp - 1))
+        exact[brk:] = exact[brk] + (knots[brk:] - knots[brk]) * slope * (1.0 - float(rng.choice([1e-7, 1e-5, 1e-3])))
+    U = exact.astype(np.float32)                    # rounded exact line(s)
+    if kind >= 2:                                   # plus or minus a few ulps of noise
+        bits = U.view(np.int32) + rng.integers(-2, 3, size=Gp).astype(np.int32)
+        U = np.maximum(bits, 0).view(np.float32)
+    U = np.maximum.accumulate(U)
+    U[0] = 0.0
+    return knots.astype(np.int32), U.astype(np.float32)
+
+
+def test_scan_equals_vertex_definition_on_near_collinear_curves():
+    """10 000 seeded curves of rounded straight lines with knots up to 2^20: the sequential scan
+    and the order-free vertex definition must name the same vertices even where chords differ
+    only in their last bits."""
+    rng = np.random.default_rng(20260208)
+    n_nontrivial = 0
+    for _ in range(10000):
+        knots, U = _near_collinear_curve(rng)
+        a, b = O.concave_hull(knots, U), _vertices_by_chords(knots, U)
+        assert a == b, (knots.tolist(), U.tolist())
+        n_nontrivial += len(a) > 2
+    assert n_nontrivial > 1000          # the family is not all straight lines
 
 
 def test_collinear_knots_are_not_vertices():
@@ -95,9 +141,22 @@ def test_collinear_knots_are_not_vertices():
     U = np.array([0, 2, 4, 5, 6, 6], dtype=np.float32)
     assert O.concave_hull(knots, U) == [0, 2, 4, 5]
     assert O.marginal_gains(knots, U) == [(0, 2, 2.0), (2, 4, 1.0), (4, 5, 0.0)]
-    assert _monotone_chain(knots, U) == [0, 2, 4, 5]
+    assert _vertices_by_chords(knots, U) == [0, 2, 4, 5]
     # a straight line has only its end points
     assert O.concave_hull(knots, np.arange(6, dtype=np.float32)) == [0, 5]
+
+
+def test_pooling_cascades_and_uses_the_pooled_blocks_own_chord():
+    """Hand-worked: unequal knot spacing and a late steep interval that pools three blocks.
+    knots 0 1 4 6 7, U 0 3 6 7 12: interval gains 3, 1, 1/2, 5.  The last interval (gain 5) pools
+    with (4,6] -> chord over (4,7] = 2 > 1, pools with (1,4] -> chord over (1,7] = 3/2 < 3: stop.
+    Vertices 0, 1, 4(end); gains 3 and 3/2.  (An unweighted mean of pooled gains, or a single
+    pooling step, gives something else.)"""
+    knots = np.array([0, 1, 4, 6, 7], np.int32)
+    U = np.array([0, 3, 6, 7, 12], np.float32)
+    assert O.concave_hull(knots, U) == [0, 1, 4]
+    assert O.marginal_gains(knots, U) == [(0, 1, 3.0), (1, 7, 1.5)]
+    assert _vertices_by_chords(knots, U) == [0, 1, 4]
 
 
 # --- unit-level PAVA (textbook pool-adjacent-violators on the marginal decreases) ----------

@@ -72,10 +72,18 @@ MUTANTS = {
                             lambda: TA.test_handworked_utility_curve_and_properties()),
     "sink_not_forced": ("s[:, :min(n_sink, L)] = np.inf", "pass",
                         lambda: TS.test_brute_force_definition()),
-    "hull_keeps_collinear": ("if steepness_in > steepness_out:", "if steepness_in >= steepness_out:",
+    "hull_keeps_collinear": ("<= _slope(knots, U, ends[-2], ends[-1]):", "< _slope(knots, U, ends[-2], ends[-1]):",
                              lambda: TA.test_collinear_knots_are_not_vertices()),
-    "hull_local_only": ("steepness_in = chord[:g, g].min()", "steepness_in = chord[g - 1, g]",
-                        lambda: TA.test_vertex_definition_equals_monotone_chain(0)),
+    "hull_pools_only_once": ("while len(ends) >= 3 and _slope(", "if len(ends) >= 3 and _slope(",
+                             lambda: TA.test_pooling_cascades_and_uses_the_pooled_blocks_own_chord()),
+    "hull_compares_last_interval_not_pooled_block": ("<= _slope(knots, U, ends[-2], ends[-1]):",
+                                                     "<= _slope(knots, U, g - 1, g):",
+                                                     lambda: TA.test_pooling_cascades_and_uses_the_pooled_blocks_own_chord()),
+    "hull_lower_instead_of_upper": ("<= _slope(knots, U, ends[-2], ends[-1]):", ">= _slope(knots, U, ends[-2], ends[-1]):",
+                                    lambda: TA.test_handworked_hull_and_gains()),
+    "gain_run_over_rise": ("return float((np.float64(U[b]) - np.float64(U[a])) / np.float64(int(knots[b]) - int(knots[a])))",
+                           "return float(np.float64(int(knots[b]) - int(knots[a])) / (np.float64(U[b]) - np.float64(U[a]) + 1e-30))",
+                           lambda: TA.test_handworked_hull_and_gains()),
     "segment_owner_off_by_one": ("if lo < u <= hi:", "if lo <= u < hi:",
                                  lambda: TA.test_handworked_hull_and_gains()),
     "head_tie_highest_first": ("h = int(np.argmax(nxt)) ", "h = int(len(nxt) - 1 - np.argmax(nxt[::-1])) ",
@@ -90,9 +98,6 @@ MUTANTS = {
     "topk_smallest": ('order = np.argsort(-s.astype(np.float64), kind="stable")',
                       'order = np.argsort(s.astype(np.float64), kind="stable")',
                       lambda: TA.test_select_brute_force_with_ties(0)),
-    "chord_transposed": ("chord = (u[None, :] - u[:, None]) / (n[None, :] - n[:, None])",
-                         "chord = ((u[None, :] - u[:, None]) / (n[None, :] - n[:, None])).T * -1",
-                         lambda: TA.test_handworked_hull_and_gains()),
 }
 
 
