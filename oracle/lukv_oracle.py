@@ -198,14 +198,16 @@ def allocate(curves: np.ndarray, knots: np.ndarray, b_min: np.ndarray, b_max: np
     b_min/b_max [NH].  Every head first receives b_min units (minimum retention,
     App. E); then one unit at a time goes to the head whose next unit has the largest
     gain, until sum(budgets) = B.  Equal gains: lowest head index first.
-    Returns (budgets int32 [NH], status); status 1 = infeasible (budgets = b_min).
+    Returns (budgets int32 [NH], status); status 1 = infeasible (budgets = b_min): B outside
+    [sum b_min, sum min(b_max, last knot)], or a bound that is no retention count (b_min < 0 or
+    b_min above the head's cap).
     """
     NH = curves.shape[0]
     segs = [marginal_gains(knots[h], curves[h]) for h in range(NH)]
     budgets = np.array([int(x) for x in b_min], dtype=np.int64)
     cap = np.minimum(np.array([int(x) for x in b_max], dtype=np.int64), knots[:, -1].astype(np.int64))
     R = int(B) - int(budgets.sum())
-    if R < 0 or R > int(np.maximum(cap - budgets, 0).sum()) or np.any(budgets > cap):
+    if R < 0 or R > int(np.maximum(cap - budgets, 0).sum()) or np.any(budgets > cap) or np.any(budgets < 0):
         return budgets.astype(np.int32), 1
 
     def next_gain(h: int) -> float:

@@ -60,6 +60,9 @@ def test_infeasible_budgets_flagged():
     assert O.allocate(U, knots, zero, four, 9)[1] == 1
     b, st = O.allocate(U, knots, np.full(2, 3, np.int32), four, 5)
     assert st == 1 and b.tolist() == [3, 3]
+    # a negative minimum retention is no retention count: flagged, handed back unchanged
+    b, st = O.allocate(U, knots, np.array([-1, 0], np.int32), four, 3)
+    assert st == 1 and b.tolist() == [-1, 0]
 
 
 # --- the hull by the definition of a strict vertex: a second, order-free construction ---------
