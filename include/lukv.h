@@ -119,8 +119,10 @@ int lukv_allocate(int32_t n_problems, int32_t n_heads, int32_t n_grid,
  * position), and gather their K and V rows.
  *   pooled   device float32 [n_layers][n_kv_heads][total_tokens] (no NaN)
  *   budgets  device int32 [n_heads_total], offsets device int64 [n_heads_total+1]
- *   out_rows rows the three outputs hold (normally offsets[n_heads_total]); a row at or beyond
- *            it is never written, and LUKV_ST_CLAMPED is raised instead
+ *   out_rows rows the three outputs hold (normally offsets[n_heads_total]); only rows in
+ *            [0, out_rows) are ever written: a row at or beyond out_rows is dropped, a head whose
+ *            offsets[hi] is negative writes nothing at all, and LUKV_ST_CLAMPED is raised instead.
+ *            Offsets need not be monotone (heads may then overwrite each other's rows)
  *   kept_idx device int32 [out_rows]: kept_idx[offsets[hi] + r] = r-th kept position (within its
  *            sequence, ascending)
  *   k_out, v_out device, dtype, [out_rows][head_dim]: row offsets[hi]+r, contiguous
@@ -135,7 +137,10 @@ int lukv_select_compact(const lukv_config* cfg, const float* pooled, const int32
  * (layer, kv_head)) -> score -> select -> compact, enqueued back to back.
  * Arguments as above; pooled may be NULL (scores then stay in the workspace).  kept_idx, k_out
  * and v_out hold sum(B_total) rows.
- *   status device int32 [n_seqs + 1]: [s] allocation status of sequence s, [n_seqs] selection. */
+ *   status device int32 [n_seqs + 1]: [s] allocation status of sequence s, [n_seqs] selection.
+ * The selection uses every budget clamped to [0, L] (LUKV_ST_CLAMPED if one was outside, which
+ * can only happen for an infeasible problem whose b_min is itself out of range), and `offsets`
+ * is the prefix sum of the clamped budgets, so no row outside [0, sum(B_total)) is written. */
 int lukv_evict(const lukv_config* cfg, const void* q_win, const void* k, const void* v,
                int32_t n_grid, const float* curves, const int32_t* knots,
                const int32_t* b_min, const int32_t* b_max, const int64_t* B_total,
@@ -225,19 +230,6 @@ int lukv_decode_workspace_bytes(const lukv_config* cfg, int64_t* bytes);
 int lukv_decode_attention(const lukv_config* cfg, const void* q_dec, const void* k_packed,
                           const void* v_packed, const int64_t* offsets, float* out, void* ws,
                           int64_t ws_bytes, void* stream);
-
-/* Instrumentation for benchmarks (process-wide, not thread-safe; for callers that time the path,
- * not part of the method).  While events are set, the main kernel of stage i of every call is
- * launched with events[2*i] as its start event and events[2*i+1] as its stop event (hipEvent_t,
- * created by the caller, passed as void*): hipEventElapsedTime(start, stop) is then that kernel's
- * own duration, as a profiler reports it.  Entries that are NULL or beyond n_events are skipped.
- * The array must stay valid until lukv_set_stage_events(NULL, 0).  Stages: allocate (the budget
- * kernel of a stand-alone lukv_allocate), score_stats, score_accum, pool (lukv_score only),
- * sel_hist, sel_tail, sel_emit (lukv_stage_name gives the same names; "" when out of range). */
-#define LUKV_NUM_STAGES 7
-#define LUKV_NUM_STAGE_EVENTS (2 * LUKV_NUM_STAGES)
-int lukv_set_stage_events(void* const* events, int32_t n_events);
-const char* lukv_stage_name(int32_t stage);
 
 /* Static description of a return code. */
 const char* lukv_strerror(int code);

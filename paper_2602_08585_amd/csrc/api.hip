@@ -143,16 +143,6 @@ WsLayout make_layout(const HostCfg& hc, int32_t n_grid, bool alloc_only) {
   return w;
 }
 
-static void* const* g_stage_events = nullptr;
-static int g_n_stage_events = 0;
-
-void stage_events(int stage, hipEvent_t* start, hipEvent_t* stop) {
-  *start = *stop = nullptr;
-  if (!g_stage_events) return;
-  if (2 * stage < g_n_stage_events) *start = static_cast<hipEvent_t>(g_stage_events[2 * stage]);
-  if (2 * stage + 1 < g_n_stage_events) *stop = static_cast<hipEvent_t>(g_stage_events[2 * stage + 1]);
-}
-
 static int check_ws(const WsLayout& lay, const void* ws, int64_t ws_bytes) {
   if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u) || ws_bytes < lay.total) return LUKV_EWORKSPACE;
   return LUKV_OK;
@@ -433,19 +423,6 @@ int lukv_decode_attention(const lukv_config* cfg, const void* q_dec, const void*
   if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u) || ws_bytes < decode_workspace_bytes(hc))
     return LUKV_EWORKSPACE;
   return launch_decode(hc, q_dec, k_packed, v_packed, offsets, out, (char*)ws, static_cast<hipStream_t>(stream));
-}
-
-int lukv_set_stage_events(void* const* events, int32_t n_events) {
-  if (n_events < 0 || (n_events > 0 && !events)) return LUKV_EINVAL;
-  g_stage_events = n_events ? events : nullptr;
-  g_n_stage_events = n_events;
-  return LUKV_OK;
-}
-
-const char* lukv_stage_name(int32_t stage) {
-  static const char* const names[kNumStages] = {
-      "allocate", "score_stats", "score_accum", "pool", "sel_hist", "sel_tail", "sel_emit"};
-  return stage >= 0 && stage < kNumStages ? names[stage] : "";
 }
 
 const char* lukv_strerror(int code) {

@@ -331,8 +331,14 @@ __global__ __launch_bounds__(1024) void sel_tail_kernel(SelGeom sg, SeqTab tab, 
   int kb = budgets[hi];
   const uint2 dig = head_dig[hi];
   long long acc = 0;
+  // row offsets are sums of the budgets as the selection uses them (clamped to [0, L]), so a
+  // budget that the allocation left out of range can never move a later head's rows out of bounds
+  const int heads_per_seq = sg.n_kv_heads * sg.n_layers;
   if (offsets_out)
-    for (int h2 = t; h2 < hi; h2 += 1024) acc += budgets[h2];
+    for (int h2 = t; h2 < hi; h2 += 1024) {
+      const int s2 = h2 / heads_per_seq, L2 = tab.cu[s2 + 1] - tab.cu[s2], b2 = budgets[h2];
+      acc += b2 < 0 ? 0 : (b2 > L2 ? L2 : b2);
+    }
 
   // suffix counts of the head: thread t owns packed word 1023-t, bins 2047-2t (high half) and
   // 2046-2t; C[b] = keys of the head in bins >= b
@@ -362,7 +368,7 @@ __global__ __launch_bounds__(1024) void sel_tail_kernel(SelGeom sg, SeqTab tab, 
     long long tot = 0;
     for (int w2 = 0; w2 < 16; ++w2) tot += osum[w2];
     offsets_out[hi] = tot;
-    if (hi == n_heads_total - 1) offsets_out[n_heads_total] = tot + budgets[hi];
+    if (hi == n_heads_total - 1) offsets_out[n_heads_total] = tot + (kb < 0 ? 0 : (kb > L ? L : kb));
   }
   if (kb < 0 || kb > L) {
     if (t == 0) atomicOr(status, LUKV_ST_CLAMPED);
@@ -501,16 +507,18 @@ __global__ __launch_bounds__(256) void sel_emit_kernel(SelGeom sg, SeqTab tab, c
   unsigned pos = (unsigned)__popcll(km & lt_mask);
   for (int w2 = 0; w2 < wave; ++w2) pos += wkeep[w2];
   unsigned n_keep = wkeep[0] + wkeep[1] + wkeep[2] + wkeep[3];
+  // a head whose row offset is negative (caller-supplied offsets) writes nothing at all
+  const bool before_start = head_row0 < 0;
   if (keep) {
     list[pos] = j;
-    if (row0 + pos < out_rows) kept_idx[row0 + pos] = j;
+    if (!before_start && row0 + pos < out_rows) kept_idx[row0 + pos] = j;
   }
   __syncthreads();
 
-  // rows beyond the caller's capacity are dropped and flagged, never written
-  if (row0 + n_keep > out_rows) {
+  // rows outside [0, out_rows) are dropped and flagged, never written
+  if (before_start || row0 + n_keep > out_rows) {
     if (threadIdx.x == 0) atomicOr(status, LUKV_ST_CLAMPED);
-    n_keep = row0 < out_rows ? (unsigned)(out_rows - row0) : 0u;
+    n_keep = before_start ? 0u : (row0 < out_rows ? (unsigned)(out_rows - row0) : 0u);
   }
   // gather: 16 bytes per lane, ROW_BYTES/16 lanes per row, four K and four V rows per thread
   constexpr int kLanesPerRow = ROW_BYTES / 16;

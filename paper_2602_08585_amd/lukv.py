@@ -35,7 +35,9 @@ EXPORTS = ("lukv_workspace_bytes", "lukv_allocate_workspace_bytes", "lukv_score"
            "lukv_select_compact", "lukv_evict", "lukv_score_lse", "lukv_evict_lse",
            "lukv_profile_workspace_bytes", "lukv_profile_curves", "lukv_profile_build", "lukv_budgets_from_profile",
            "lukv_evict_budgets", "lukv_decode_workspace_bytes", "lukv_decode_attention",
-           "lukv_set_stage_events", "lukv_stage_name", "lukv_strerror")
+           "lukv_strerror")
+# include/lukv_bench.h: instrumentation for programs that time the path
+BENCH_EXPORTS = ("lukv_set_stage_events", "lukv_stage_name", "lukv_bench_stream_read", "lukv_bench_copy")
 LUKV_NUM_STAGES = 7
 LUKV_NUM_STAGE_EVENTS = 2 * LUKV_NUM_STAGES
 
@@ -90,10 +92,12 @@ def load_library() -> ctypes.CDLL:
     lib.lukv_evict_budgets.argtypes = [CP, P, P, P, P, P, P, I64, P, P, P, P, P, P, I64, P]
     lib.lukv_decode_workspace_bytes.argtypes = [CP, ctypes.POINTER(I64)]
     lib.lukv_decode_attention.argtypes = [CP, P, P, P, P, P, P, I64, P]
+    lib.lukv_bench_stream_read.argtypes = [P, I64, P, I32, P]
+    lib.lukv_bench_copy.argtypes = [P, P, I64, I32, P]
     lib.lukv_set_stage_events.argtypes = [ctypes.POINTER(ctypes.c_void_p), I32]
     lib.lukv_stage_name.argtypes = [I32]
     lib.lukv_stage_name.restype = ctypes.c_char_p
-    for name in EXPORTS:
+    for name in EXPORTS + BENCH_EXPORTS:
         if name not in ("lukv_strerror", "lukv_stage_name"):
             getattr(lib, name).restype = ctypes.c_int
     lib.lukv_strerror.argtypes = [ctypes.c_int]
@@ -327,3 +331,13 @@ def lukv_set_stage_events(events) -> None:
 
 def lukv_stage_name(stage: int) -> str:
     return load_library().lukv_stage_name(int(stage)).decode()
+
+
+def lukv_bench_stream_read(src, nbytes: int, sink, blocks: int, stream=None) -> None:
+    _check(load_library().lukv_bench_stream_read(_ptr(src), int(nbytes), _ptr(sink), int(blocks), _stream(stream)),
+           "lukv_bench_stream_read")
+
+
+def lukv_bench_copy(src, dst, nbytes: int, blocks: int, stream=None) -> None:
+    _check(load_library().lukv_bench_copy(_ptr(src), _ptr(dst), int(nbytes), int(blocks), _stream(stream)),
+           "lukv_bench_copy")

@@ -191,11 +191,17 @@ def make_decode_queries(wl: Workload, layers: Optional[List[int]] = None) -> np.
     return _store(out, wl.dtype)
 
 
-def make_qkv(wl: Workload, layers: Optional[List[int]] = None) -> Dict[str, np.ndarray]:
+def make_qkv(wl: Workload, layers: Optional[List[int]] = None, workers: int = 1) -> Dict[str, np.ndarray]:
     """Stack `make_layer_qkv` over layers: q_win [NL, H_q, n_seqs*w, d],
-    k, v [NL, H_kv, total_len, d]."""
+    k, v [NL, H_kv, total_len, d].  workers > 1 draws layers on that many host threads (every
+    layer has its own keyed generator, so the result does not depend on it)."""
     layers = list(range(wl.n_layers)) if layers is None else layers
-    parts = [make_layer_qkv(wl, l) for l in layers]
+    if workers > 1 and len(layers) > 1:
+        from concurrent.futures import ThreadPoolExecutor
+        with ThreadPoolExecutor(max_workers=workers) as pool:
+            parts = list(pool.map(lambda l: make_layer_qkv(wl, l), layers))
+    else:
+        parts = [make_layer_qkv(wl, l) for l in layers]
     return {key: np.stack([p[key] for p in parts]) for key in ("q_win", "k", "v")}
 
 

@@ -29,9 +29,9 @@ def host_bits(t: torch.Tensor) -> np.ndarray:
 class Problem:
     """A workload's inputs on host and device, plus its lukv Config and workspace."""
 
-    def __init__(self, wl: synth.Workload, layers=None, data=None, alloc=None):
+    def __init__(self, wl: synth.Workload, layers=None, data=None, alloc=None, workers=1):
         self.wl = wl
-        self.data = synth.make_qkv(wl, layers) if data is None else data
+        self.data = synth.make_qkv(wl, layers, workers=workers) if data is None else data
         self.alloc = synth.make_allocation_inputs(wl) if alloc is None else alloc
         self.q = dev(self.data["q_win"])
         self.k = dev(self.data["k"])

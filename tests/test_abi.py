@@ -11,17 +11,18 @@ from paper_2602_08585_amd import lukv, synth
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def _declared():
-    text = open(os.path.join(ROOT, "include", "lukv.h")).read()
+def _declared(header):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(lukv_[a-z_]+)\s*\(", text)))
 
 
 def test_library_exports_every_declared_symbol():
     lib = lukv.load_library()
-    names = _declared()
-    assert set(names) == set(lukv.EXPORTS)
-    for n in names:
+    assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["lukv.h", "lukv_bench.h"]
+    assert set(_declared("lukv.h")) == set(lukv.EXPORTS)
+    assert set(_declared("lukv_bench.h")) == set(lukv.BENCH_EXPORTS)
+    for n in lukv.EXPORTS + lukv.BENCH_EXPORTS:
         assert hasattr(lib, n), n
 
 

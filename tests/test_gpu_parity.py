@@ -317,6 +317,70 @@ def test_select_budget_extremes_and_clamp():
     assert np.array_equal(kept[L:L + 2], O.select(pooled[1, 0], 2))
 
 
+def _guarded(rows, d, dtype, guard=64):
+    """Output buffers with `guard` rows of sentinel before and after the part handed to the library."""
+    idx = torch.full((rows + 2 * guard,), -7, dtype=torch.int32, device="cuda")
+    ko = torch.full((rows + 2 * guard, d), 1.0, dtype=dtype, device="cuda")
+    vo = torch.full((rows + 2 * guard, d), 1.0, dtype=dtype, device="cuda")
+
+    def untouched():
+        for t, sentinel in ((idx, -7), (ko, 1.0), (vo, 1.0)):
+            assert bool((t[:guard] == sentinel).all()) and bool((t[guard + rows:] == sentinel).all())
+
+    return idx[guard:guard + rows], ko[guard:guard + rows], vo[guard:guard + rows], untouched
+
+
+def test_rows_outside_the_output_are_never_written():
+    """Negative or too large row offsets (caller-supplied, or from an infeasible allocation whose
+    b_min is itself negative) are flagged and write nothing outside [0, out_rows)."""
+    print("case rows outside the output", flush=True)
+    wl = small("bf16_g4_w32")
+    p = Problem(wl)
+    L, NL, H, d = wl.seq_lens[0], wl.n_layers, wl.n_kv_heads, wl.head_dim
+    rng = np.random.default_rng(78)
+    pooled = rng.random((NL, H, L)).astype(np.float32)
+    pooled[:, :, -wl.window:] = np.inf
+    budgets = np.array([40, 50, 60, 70], np.int32)
+    rows = 120
+    # head 0 starts before the buffer, head 1 is in range, head 2 runs over the end, head 3 starts beyond it
+    offsets = np.array([-5, 10, rows - 20, rows + 7, rows + 77], np.int64)
+    idx, ko, vo, untouched = _guarded(rows, d, p.k.dtype)
+    status = torch.full((1,), -7, dtype=torch.int32, device="cuda")
+    lukv.lukv_select_compact(p.cfg, dev(pooled), dev(budgets), dev(offsets), p.k, p.v, rows, idx, ko, vo, status, p.ws)
+    torch.cuda.synchronize()
+    assert int(status[0]) == lukv.LUKV_ST_CLAMPED
+    untouched()
+    got = idx.cpu().numpy()
+    assert np.all(got[:10] == -7), "a head with a negative offset writes nothing"
+    want1 = O.select(pooled[0, 1], 50)
+    assert np.array_equal(got[10:60], want1)
+    assert np.array_equal(host_bits(ko)[10:60], p.data["k"][0, 1][want1])
+    assert np.array_equal(got[rows - 20:], O.select(pooled[1, 0], 60)[:20])
+    # fused path: one head's b_min is negative, so the allocation is infeasible and hands the
+    # b_min back as budgets; the selection clamps them and its offsets stay inside the output
+    alloc = {k: v.copy() for k, v in p.alloc.items()}
+    alloc["b_min"][0, 1] = -9
+    q = Problem(wl, data=p.data, alloc=alloc)
+    rows = sum(q.B)
+    idx, ko, vo, untouched = _guarded(rows, d, p.k.dtype)
+    out = q.new_outputs()
+    lukv.lukv_evict(q.cfg, q.q, q.k, q.v, wl.n_grid, q.curves, q.knots, q.b_min, q.b_max, q.B, out["budgets"],
+                    out["offsets"], idx, ko, vo, None, out["status"], q.ws)
+    torch.cuda.synchronize()
+    assert int(out["status"][0]) == lukv.LUKV_ST_INFEASIBLE and int(out["status"][1]) == lukv.LUKV_ST_CLAMPED
+    assert np.array_equal(out["budgets"].cpu().numpy(), alloc["b_min"][0])
+    clamped = np.maximum(alloc["b_min"][0], 0)
+    assert np.array_equal(out["offsets"].cpu().numpy(), O.offsets_of(clamped))
+    untouched()
+    got = idx.cpu().numpy()
+    offs = O.offsets_of(clamped)
+    for hi in range(NL * H):
+        l, c = divmod(hi, H)
+        a, b = int(offs[hi]), int(offs[hi + 1])
+        assert np.all(np.diff(got[a:b]) > 0)
+        assert np.array_equal(host_bits(ko)[a:b], p.data["k"][l, c][got[a:b]])
+
+
 def _adversarial_scores(kind, rng, shape):
     """Score distributions that stress the radix select: candidates by the thousand, a digit
     that does not discriminate, clamped end bins, both signs, infinities, zeros of both signs."""
@@ -400,6 +464,13 @@ def test_host_side_refusals_enqueue_nothing():
 
 # ---- full-size headline configuration -------------------------------------------------------
 
+# Near-threshold swaps the literal recipe may show per 8B/32k layer.  With entries N(0,1)/sqrt(d)
+# the logits have a spread of about 1/d, so the pooled scores of a head lie within about 1e-3
+# (relative) of one another and a few dozen of its 32768 positions sit inside the BAND around the
+# k-th score; 10 swaps in 52428 rows were seen.  More than this bound means the scores drifted.
+MAX_BAND_SWAPS_PER_LAYER = 40
+
+
 def test_evict_full_size_8b_32k():
     """The configuration bench.py times (one 8B-shaped layer, L=32768), checked in full."""
     print("case 8b_32k full size", flush=True)
@@ -407,10 +478,11 @@ def test_evict_full_size_8b_32k():
     p = Problem(wl)
     out = p.evict()
     ref = p.oracle()
-    # literal recipe: scores sit within ~1e-3 of each other, so fp32-vs-fp64 rounding may move
-    # a handful of near-threshold positions; they must stay inside the 1e-3 band
-    n_band = _check_evict(p, out, ref, band=1e-3)
+    # literal recipe: fp32-vs-fp64 rounding may move a handful of near-threshold positions; they
+    # must stay inside the derived error band, and there may only be a handful
+    n_band = _check_evict(p, out, ref, band=BAND)
     print("8b_32k band-only index differences:", n_band, "of", int(ref["offsets"][-1]))
+    assert n_band <= MAX_BAND_SWAPS_PER_LAYER
     # and bit-exact selection on the oracle's own scores at full size
     pooled = np.stack([ref["pooled"][(0, 0)]])
     out2 = p.new_outputs()
@@ -421,6 +493,20 @@ def test_evict_full_size_8b_32k():
     assert np.array_equal(out2["kept_idx"].cpu().numpy(), want_idx)
     want_k = np.concatenate([ref["k_out"][(0, 0, c)] for c in range(wl.n_kv_heads)])
     assert np.array_equal(host_bits(out2["k_out"]), want_k)
+
+
+def test_evict_full_size_8b_32k_well_separated_scores_are_bit_exact():
+    """The headline shape on inputs whose scores are well separated (queries scaled by d, logits
+    ~ N(0,1)): the fused call and the lse variant must reproduce the oracle's kept indices and
+    compacted rows exactly, all 8 heads, no band."""
+    print("case 8b_32k full size, well-separated scores", flush=True)
+    wl = dataclasses.replace(synth.workload("8b_32k"), q_gain=128.0, name="8b_32k_peaky")
+    p = Problem(wl)
+    ref = p.oracle()
+    assert _check_evict(p, p.evict(), ref) == 0
+    lse_h = p.oracle_lse()
+    ref_l = p.oracle(lse=lse_h)
+    assert _check_evict(p, p.evict_lse(dev(lse_h)), ref_l) == 0
 
 
 def _check_sampled_heads(p, out, samples, band):
@@ -471,8 +557,9 @@ def test_evict_full_size_long_context_layer():
     wl = dataclasses.replace(synth.workload("long_128k"), n_layers=1, name="long_128k_layer")
     p = Problem(wl)
     out = p.evict()
-    n_band = _check_sampled_heads(p, out, [(0, 0, 1), (0, 0, 6)], band=1e-3)
+    n_band = _check_sampled_heads(p, out, [(0, 0, 1), (0, 0, 6)], band=BAND)
     print("long_128k band-only index differences in the sampled heads:", n_band)
+    assert n_band <= 16
 
 
 @pytest.mark.timeout(400)
@@ -484,8 +571,9 @@ def test_evict_full_size_ragged_batch():
     out = p.evict()
     order = np.argsort(wl.seq_lens)
     samples = [(int(order[0]), 0, 0), (int(order[1]), 0, 5), (int(order[-1]), 0, 3)]
-    n_band = _check_sampled_heads(p, out, samples, band=1e-3)
+    n_band = _check_sampled_heads(p, out, samples, band=BAND)
     print("batched band-only index differences in the sampled heads:", n_band)
+    assert n_band <= 16
 
 
 @pytest.mark.timeout(400)
@@ -496,8 +584,100 @@ def test_evict_full_size_four_layers_global_budget():
     wl = dataclasses.replace(synth.workload("8b_full_20"), n_layers=4, name="8b_full_20_4layers")
     p = Problem(wl)
     out = p.evict()
-    n_band = _check_sampled_heads(p, out, [(0, 0, 2), (0, 3, 7), (0, 2, 4)], band=1e-3)
+    n_band = _check_sampled_heads(p, out, [(0, 0, 2), (0, 3, 7), (0, 2, 4)], band=BAND)
     print("8b_full_20 (4 layers) band-only index differences in the sampled heads:", n_band)
+    assert n_band <= 16
+
+
+@pytest.mark.timeout(600)
+def test_evict_full_prefill_32_layers_both_ratios():
+    """The full-prefill configuration as the call that is benchmarked with --layers 32: 32 layers
+    of L = 32768 in ONE call, one global allocation over all 256 layer-heads, at 20 % and at 10 %.
+    Every layer and head is compared with the oracle; budgets for all 256 heads bit-exact."""
+    for name in ("8b_full_20", "8b_full_10"):
+        print("case", name, "all 32 layers in one call", flush=True)
+        wl = synth.workload(name)
+        if name == "8b_full_20":
+            p = Problem(wl, workers=8)
+        else:
+            p = Problem(wl, data=p.data)         # same seeded Q/K/V, other budget
+        out = p.evict()
+        ref = p.oracle()
+        n_band = _check_evict(p, out, ref, band=BAND)
+        print(name, "band-only index differences over 32 layers:", n_band, "of", int(ref["offsets"][-1]), flush=True)
+        assert n_band <= 32 * MAX_BAND_SWAPS_PER_LAYER
+        assert int(ref["budgets"].min()) < int(ref["budgets"].max())     # uneven heads
+
+
+@pytest.mark.timeout(900)
+def test_evict_long_context_32_layers():
+    """The long-context configuration as one call: 32 layers of L = 131072 (w = 64, 5 %), one
+    global allocation over 256 layer-heads.  Inputs are drawn layer by layer (host threads) and
+    uploaded; budgets and offsets for all 256 heads are compared with the oracle bit for bit,
+    layers 0, 15 and 31 are compared with the oracle in full (scores, kept sets, rows), and every
+    head of every layer is checked on the device for what holds at any size (count = budget,
+    ascending positions, sink and window kept, compacted rows bitwise the source rows)."""
+    from concurrent.futures import ThreadPoolExecutor
+    print("case long_128k, 32 layers in one call", flush=True)
+    wl = synth.workload("long_128k")
+    NL, H, Hq, L, d, w = wl.n_layers, wl.n_kv_heads, wl.n_q_heads, wl.seq_lens[0], wl.head_dim, wl.window
+    oracle_layers = (0, 15, 31)
+    K = torch.empty((NL, H, L, d), dtype=torch.bfloat16, device="cuda")
+    V = torch.empty_like(K)
+    Q = torch.empty((NL, Hq, w, d), dtype=torch.bfloat16, device="cuda")
+    host = {}
+    with ThreadPoolExecutor(max_workers=8) as pool:
+        for l, part in zip(range(NL), pool.map(lambda l: synth.make_layer_qkv(wl, l), range(NL))):
+            K[l].copy_(dev(part["k"]))
+            V[l].copy_(dev(part["v"]))
+            Q[l].copy_(dev(part["q_win"]))
+            if l in oracle_layers:
+                host[l] = part
+            if l % 8 == 7:
+                print("  layers drawn:", l + 1, flush=True)
+    a = synth.make_allocation_inputs(wl)
+    cfg = lukv.Config.for_tensors(Q, K, w, wl.cu_seqlens.tolist(), wl.pool_kernel, wl.n_sink)
+    ws = lukv.alloc_workspace(lukv.lukv_workspace_bytes(cfg, wl.n_grid))
+    rows = int(a["B"].sum())
+    n_hi = NL * H
+    budgets = torch.full((n_hi,), -7, dtype=torch.int32, device="cuda")
+    offsets = torch.full((n_hi + 1,), -7, dtype=torch.int64, device="cuda")
+    kept = torch.full((rows,), -7, dtype=torch.int32, device="cuda")
+    ko = torch.zeros((rows, d), dtype=torch.bfloat16, device="cuda")
+    vo = torch.zeros((rows, d), dtype=torch.bfloat16, device="cuda")
+    pooled = torch.full((NL, H, L), float("nan"), dtype=torch.float32, device="cuda")
+    status = torch.full((2,), -7, dtype=torch.int32, device="cuda")
+    lukv.lukv_evict(cfg, Q, K, V, wl.n_grid, dev(a["curves"]), dev(a["knots"]), dev(a["b_min"]), dev(a["b_max"]),
+                    [int(x) for x in a["B"]], budgets, offsets, kept, ko, vo, pooled, status, ws)
+    torch.cuda.synchronize()
+    print("  call done; oracle allocation over 256 heads", flush=True)
+    assert int(status.abs().sum()) == 0
+    b_ref, st = O.allocate(a["curves"][0], a["knots"][0], a["b_min"][0], a["b_max"][0], int(a["B"][0]))
+    off_ref = O.offsets_of(b_ref)
+    assert st == 0 and np.array_equal(budgets.cpu().numpy(), b_ref) and np.array_equal(offsets.cpu().numpy(), off_ref)
+    # every head, on the device
+    sink = torch.arange(wl.n_sink, device="cuda", dtype=torch.int32)
+    win = torch.arange(L - w, L, device="cuda", dtype=torch.int32)
+    for hi in range(n_hi):
+        l, c = divmod(hi, H)
+        lo, hi_end = int(off_ref[hi]), int(off_ref[hi + 1])
+        idx = kept[lo:hi_end]
+        assert bool((idx[1:] > idx[:-1]).all()) and int(idx[0]) >= 0 and int(idx[-1]) < L
+        assert torch.equal(idx[:wl.n_sink], sink) and torch.equal(idx[-w:], win)
+        assert torch.equal(ko[lo:hi_end], K[l, c][idx.long()]) and torch.equal(vo[lo:hi_end], V[l, c][idx.long()])
+    # three layers against the oracle, all eight heads each
+    kept_h, pooled_h = kept.cpu().numpy(), pooled.cpu().numpy()
+    n_band = 0
+    for l in oracle_layers:
+        print("  oracle layer", l, flush=True)
+        S = O.score(O.decode(host[l]["q_win"]), O.decode(host[l]["k"]), H, w, wl.pool_kernel, wl.n_sink)
+        assert_scores_close(pooled_h[l], S)
+        for c in range(H):
+            hi = l * H + c
+            lo, hi_end = int(off_ref[hi]), int(off_ref[hi + 1])
+            n_band += check_band(kept_h[lo:hi_end], O.select(S[c], int(b_ref[hi])), S[c], BAND)
+    print("long_128k (32 layers) band-only index differences in layers 0/15/31:", n_band)
+    assert n_band <= 3 * MAX_BAND_SWAPS_PER_LAYER
 
 
 def _calibration_curves(wl, n_queries):
@@ -682,8 +862,9 @@ def test_evict_longest_sequence_the_library_takes():
                         keep_ratio=0.03, n_grid=32, heavy_frac=0.001, seed=77, q_gain=64.0)
     p = Problem(wl)
     out = p.evict()
-    n_band = _check_sampled_heads(p, out, [(0, 0, 0)], band=1e-3)
+    n_band = _check_sampled_heads(p, out, [(0, 0, 0)], band=BAND)
     print("L = 2^20 band-only index differences:", n_band)
+    assert n_band == 0          # well-separated scores (queries scaled by d)
     # one token more is refused on the host
     with pytest.raises(lukv.LukvError):
         lukv.lukv_workspace_bytes(dataclasses.replace(p.cfg, cu_seqlens=[0, (1 << 20) + 1]), wl.n_grid)
@@ -787,22 +968,14 @@ def test_evict_replays_from_a_hip_graph():
 
 
 def test_lse_variant_full_size_8b_32k():
-    """The configuration bench.py times as `lse_variant`: budgets bit-exact, sampled heads against
-    the oracle run with the same log-sum-exp."""
+    """The configuration bench.py times as `lse_variant`, checked in full against the oracle run
+    with the same log-sum-exp."""
     print("case 8b_32k with lse", flush=True)
     wl = synth.workload("8b_32k")
     p = Problem(wl)
     lse_h = p.oracle_lse()
     out = p.evict_lse(dev(lse_h))
-    a = p.alloc
-    budgets_ref = O.allocate(a["curves"][0], a["knots"][0], a["b_min"][0], a["b_max"][0], int(a["B"][0]))[0]
-    offs = O.offsets_of(budgets_ref)
-    assert np.array_equal(out["budgets"].cpu().numpy(), budgets_ref)
-    assert int(out["status"].abs().sum()) == 0
-    kept, pooled = out["kept_idx"].cpu().numpy(), out["pooled"].cpu().numpy()
-    G, w = wl.n_q_heads // wl.n_kv_heads, wl.window
-    for c in (2, 5):
-        S = O.score(O.decode(p.data["q_win"][0, c * G:(c + 1) * G]), O.decode(p.data["k"][0, c:c + 1]), 1, w,
-                    wl.pool_kernel, wl.n_sink, lse=lse_h[0, c * G:(c + 1) * G])[0]
-        assert_scores_close(pooled[0, c], S)
-        check_band(kept[offs[c]:offs[c + 1]], O.select(S, int(budgets_ref[c])), S, 1e-3)
+    ref = p.oracle(lse=lse_h)
+    n_band = _check_evict(p, out, ref, band=BAND)
+    print("8b_32k (lse) band-only index differences:", n_band)
+    assert n_band <= MAX_BAND_SWAPS_PER_LAYER
