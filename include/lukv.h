@@ -231,6 +231,22 @@ int lukv_decode_attention(const lukv_config* cfg, const void* q_dec, const void*
                           const void* v_packed, const int64_t* offsets, float* out, void* ws,
                           int64_t ws_bytes, void* stream);
 
+/* lukv_evict for callers that cannot allocate device memory or carry a workspace around: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments
+ * and results as lukv_evict, but the scratch is a fixed array inside the library
+ * (LUKV_STATIC_SCRATCH_BYTES of device memory per GPU the library runs on, held until the process
+ * ends); the call allocates and frees nothing.  A configuration whose lukv_workspace_bytes exceeds
+ * LUKV_STATIC_SCRATCH_BYTES is refused with LUKV_EWORKSPACE (the 8B-shaped layer at 32k context
+ * needs 7.6 MiB).  Every call on a GPU uses that GPU's one array: calls that overlap in time on
+ * the same GPU (different streams or threads) race and must be serialised by the caller.  The
+ * array needs no clearing between calls (every word is written before it is read in a call). */
+#define LUKV_STATIC_SCRATCH_BYTES (16 << 20)
+int lukv_evict_static(const lukv_config* cfg, const void* q_win, const void* k, const void* v,
+                      int32_t n_grid, const float* curves, const int32_t* knots,
+                      const int32_t* b_min, const int32_t* b_max, const int64_t* B_total,
+                      int32_t* budgets, int64_t* offsets, int32_t* kept_idx,
+                      void* k_out, void* v_out, float* pooled, int32_t* status, void* stream);
+
 /* Static description of a return code. */
 const char* lukv_strerror(int code);
 

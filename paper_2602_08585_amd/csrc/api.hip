@@ -2,10 +2,38 @@
 #include <math.h>
 #include <string.h>
 
+#include <mutex>
+
 #include "alloc_device.hpp"
 #include "lukv_internal.hpp"
 
+// Scratch of lukv_evict_static: one array per GPU, inside the library's code object.  In host
+// code the name below is only a handle for hipGetSymbolAddress; kernels and launches get the
+// device address that call returned for the current device (static_scratch_ptr).
+static __device__ __align__(256) unsigned char scratch[LUKV_STATIC_SCRATCH_BYTES];
+
 namespace lukv {
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static void* g_scratch_ptr[kMaxDevices];   // device address of `scratch` on every device seen so far
+
+// Device address of the static scratch on the current device (asked once per device, with that
+// device current); nullptr when the runtime refuses.  Allocates nothing.
+static void* static_scratch_ptr() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+      (void)hipGetLastError();
+      return nullptr;
+    }
+    g_scratch_ptr[dev] = ptr;
+  }
+  return g_scratch_ptr[dev];
+}
 
 static inline int64_t align_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
 static inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -293,6 +321,24 @@ int lukv_evict(const lukv_config* cfg, const void* q_win, const void* k, const v
                     offsets, kept_idx, k_out, v_out, pooled, status, ws, ws_bytes, stream);
 }
 
+int lukv_evict_static(const lukv_config* cfg, const void* q_win, const void* k, const void* v,
+                      int32_t n_grid, const float* curves, const int32_t* knots, const int32_t* b_min,
+                      const int32_t* b_max, const int64_t* B_total, int32_t* budgets, int64_t* offsets,
+                      int32_t* kept_idx, void* k_out, void* v_out, float* pooled, int32_t* status,
+                      void* stream) {
+  // the size check comes first and touches no device: a configuration beyond the built-in
+  // scratch is refused before anything else happens
+  if (n_grid < 2 || n_grid > kMaxGrid) return LUKV_EINVAL;
+  HostCfg hc;
+  const int rc = validate_config(cfg, &hc);
+  if (rc) return rc;
+  if (make_layout(hc, n_grid, false).total > (int64_t)LUKV_STATIC_SCRATCH_BYTES) return LUKV_EWORKSPACE;
+  void* ptr = static_scratch_ptr();
+  if (!ptr) return LUKV_ELAUNCH;
+  return evict_impl(cfg, q_win, k, v, nullptr, n_grid, curves, knots, b_min, b_max, B_total, budgets,
+                    offsets, kept_idx, k_out, v_out, pooled, status, ptr, LUKV_STATIC_SCRATCH_BYTES, stream);
+}
+
 int lukv_evict_lse(const lukv_config* cfg, const void* q_win, const void* k, const void* v,
                    const float* lse, int32_t n_grid, const float* curves, const int32_t* knots,
                    const int32_t* b_min, const int32_t* b_max, const int64_t* B_total,
@@ -431,7 +477,7 @@ const char* lukv_strerror(int code) {
     case LUKV_EINVAL: return "invalid argument (null pointer, dimension, stride, alignment or limit)";
     case LUKV_EDTYPE: return "unsupported dtype or head_dim";
     case LUKV_EINFEASIBLE: return "infeasible budget";
-    case LUKV_EWORKSPACE: return "workspace missing, misaligned or too small";
+    case LUKV_EWORKSPACE: return "workspace missing, misaligned or too small (or the configuration needs more than the built-in scratch of lukv_evict_static)";
     case LUKV_ELAUNCH: return "HIP launch failed";
     default: return "unknown lukv error code";
   }

@@ -35,9 +35,10 @@ EXPORTS = ("lukv_workspace_bytes", "lukv_allocate_workspace_bytes", "lukv_score"
            "lukv_select_compact", "lukv_evict", "lukv_score_lse", "lukv_evict_lse",
            "lukv_profile_workspace_bytes", "lukv_profile_curves", "lukv_profile_build", "lukv_budgets_from_profile",
            "lukv_evict_budgets", "lukv_decode_workspace_bytes", "lukv_decode_attention",
-           "lukv_strerror")
+           "lukv_evict_static", "lukv_strerror")
 # include/lukv_bench.h: instrumentation for programs that time the path
 BENCH_EXPORTS = ("lukv_set_stage_events", "lukv_stage_name", "lukv_bench_stream_read", "lukv_bench_copy")
+LUKV_STATIC_SCRATCH_BYTES = 16 << 20
 LUKV_NUM_STAGES = 7
 LUKV_NUM_STAGE_EVENTS = 2 * LUKV_NUM_STAGES
 
@@ -92,6 +93,8 @@ def load_library() -> ctypes.CDLL:
     lib.lukv_evict_budgets.argtypes = [CP, P, P, P, P, P, P, I64, P, P, P, P, P, P, I64, P]
     lib.lukv_decode_workspace_bytes.argtypes = [CP, ctypes.POINTER(I64)]
     lib.lukv_decode_attention.argtypes = [CP, P, P, P, P, P, P, I64, P]
+    lib.lukv_evict_static.argtypes = [CP, P, P, P, I32, P, P, P, P, ctypes.POINTER(I64),
+                                      P, P, P, P, P, P, P, P]
     lib.lukv_bench_stream_read.argtypes = [P, I64, P, I32, P]
     lib.lukv_bench_copy.argtypes = [P, P, I64, I32, P]
     lib.lukv_set_stage_events.argtypes = [ctypes.POINTER(ctypes.c_void_p), I32]
@@ -250,6 +253,17 @@ def lukv_evict(cfg: Config, q_win, k, v, n_grid: int, curves, knots, b_min, b_ma
                                      _ptr(budgets), _ptr(offsets), _ptr(kept_idx), _ptr(k_out),
                                      _ptr(v_out), _ptr(pooled), _ptr(status), _ptr(ws), ws.numel(),
                                      _stream(stream)), "lukv_evict")
+
+
+def lukv_evict_static(cfg: Config, q_win, k, v, n_grid: int, curves, knots, b_min, b_max,
+                      B_total: Sequence[int], budgets, offsets, kept_idx, k_out, v_out, pooled, status,
+                      stream=None) -> None:
+    keep, Bp = _host_i64(B_total)
+    _check(load_library().lukv_evict_static(ctypes.byref(cfg.to_c()), _ptr(q_win), _ptr(k), _ptr(v), n_grid,
+                                            _ptr(curves), _ptr(knots), _ptr(b_min), _ptr(b_max), Bp,
+                                            _ptr(budgets), _ptr(offsets), _ptr(kept_idx), _ptr(k_out),
+                                            _ptr(v_out), _ptr(pooled), _ptr(status), _stream(stream)),
+           "lukv_evict_static")
 
 
 def lukv_evict_lse(cfg: Config, q_win, k, v, lse, n_grid: int, curves, knots, b_min, b_max,

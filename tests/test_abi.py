@@ -26,6 +26,20 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(lib, n), n
 
 
+def test_static_scratch_entry_point_refuses_what_does_not_fit():
+    """lukv_evict_static: a configuration whose workspace exceeds the built-in scratch is refused on
+    the host before anything touches a device."""
+    lib = lukv.load_library()
+    fake = ctypes.c_void_p(256)       # never dereferenced
+    B = (ctypes.c_int64 * 1)(1000)
+    big = _cfg(cu_seqlens=[0, 131072], stride_head=131072 * 128, stride_layer=8 * 131072 * 128)
+    assert lukv.lukv_workspace_bytes(big, 64) > lukv.LUKV_STATIC_SCRATCH_BYTES
+    assert lukv.lukv_workspace_bytes(_cfg(), 64) <= lukv.LUKV_STATIC_SCRATCH_BYTES
+    rc = lib.lukv_evict_static(ctypes.byref(big.to_c()), fake, fake, fake, 64, fake, fake, fake, fake, B,
+                               fake, fake, fake, fake, fake, None, fake, None)
+    assert rc == lukv.LUKV_EWORKSPACE
+
+
 def test_strerror_covers_codes():
     for code in (0, -1, -2, -3, -4, -5):
         assert "unknown" not in lukv.strerror(code)
