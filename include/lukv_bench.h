@@ -17,8 +17,9 @@ extern "C" {
  * own duration, as a profiler reports it.  Entries that are NULL or beyond n_events are skipped.
  * The array must stay valid until lukv_set_stage_events(NULL, 0).  Stages: allocate (the budget
  * kernel of a stand-alone lukv_allocate), score_stats, score_accum, pool (lukv_score only),
- * sel_hist, sel_tail, sel_emit (lukv_stage_name gives the same names; "" when out of range). */
-#define LUKV_NUM_STAGES 7
+ * sel_hist, sel_tail, sel_emit (selection of sequences beyond 32768 tokens), sel_head, sel_gather
+ * (selection otherwise); lukv_stage_name gives the same names, "" when out of range. */
+#define LUKV_NUM_STAGES 9
 #define LUKV_NUM_STAGE_EVENTS (2 * LUKV_NUM_STAGES)
 int lukv_set_stage_events(void* const* events, int32_t n_events);
 const char* lukv_stage_name(int32_t stage);

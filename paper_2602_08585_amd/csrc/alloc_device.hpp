@@ -30,6 +30,7 @@
 
 #pragma clang fp contract(off)
 
+
 namespace lukv {
 
 struct AllocIO {
@@ -134,6 +135,62 @@ __device__ inline void alloc_phase_a(const AllocIO& io, int p, int blk) {
     steep_out = o2 > steep_out ? o2 : steep_out;
   }
   if (live && part == 0) io.vertex[base + g] = (g == 0 || g == Gp - 1) ? 1 : (steep_in > steep_out ? 1 : 0);
+}
+
+// Phase A for one knot by one wave, in two steps so that the loads can be issued before a
+// workgroup's other loads and consumed after them: all 64 lanes call both with the same `item`
+// (flat knot index over problems, heads and grid points); lane l takes the chord to knot l
+// (grids of more than 64 points: the remaining chords are loaded in the second step).
+struct AllocKnotLoad { float u_x, u_me; int32_t n_x, n_me; };
+
+__device__ __forceinline__ AllocKnotLoad alloc_knot_load(const AllocIO& io, int64_t item) {
+  const int Gp = io.n_grid, lane = threadIdx.x & 63;
+  const int64_t hb = item / Gp * Gp;
+  const int g = (int)(item - hb), x = lane < Gp ? lane : g;
+  AllocKnotLoad ld;
+  ld.u_x = io.curves[hb + x];
+  ld.n_x = io.knots[hb + x];
+  ld.u_me = io.curves[hb + g];
+  ld.n_me = io.knots[hb + g];
+  return ld;
+}
+
+__device__ __forceinline__ void alloc_knot_finish(const AllocIO& io, int64_t item, const AllocKnotLoad& ld) {
+  const int Gp = io.n_grid, lane = threadIdx.x & 63;
+  const int64_t hb = item / Gp * Gp;
+  const int g = (int)(item - hb);
+  const double u_me = (double)ld.u_me;
+  const int n_me = ld.n_me;
+  double steep_in = INFINITY, steep_out = -INFINITY;
+  if (lane < g) {
+    steep_in = (u_me - (double)ld.u_x) / (double)(n_me - ld.n_x);
+  } else if (lane > g && lane < Gp) {
+    steep_out = ((double)ld.u_x - u_me) / (double)(ld.n_x - n_me);
+  }
+  for (int x = lane + 64; x < Gp; x += 64) {
+    if (x < g) {
+      const double s = (u_me - (double)io.curves[hb + x]) / (double)(n_me - io.knots[hb + x]);
+      steep_in = s < steep_in ? s : steep_in;
+    } else if (x > g) {
+      const double s = ((double)io.curves[hb + x] - u_me) / (double)(io.knots[hb + x] - n_me);
+      steep_out = s > steep_out ? s : steep_out;
+    }
+  }
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const double i2 = shfl_xor_f64(steep_in, o), o2 = shfl_xor_f64(steep_out, o);
+    steep_in = i2 < steep_in ? i2 : steep_in;
+    steep_out = o2 > steep_out ? o2 : steep_out;
+  }
+  if (lane == 0) io.vertex[item] = (g == 0 || g == Gp - 1) ? 1 : (steep_in > steep_out ? 1 : 0);
+}
+
+// Knots per scoring workgroup when phase A is spread over the prologues of n_wgs workgroups of
+// four waves (one knot per wave at most); 0 when the problem is too large for that.
+__host__ __device__ inline int alloc_spread_knots(int64_t n_knots, int64_t n_wgs) {
+  if (n_wgs <= 0) return 0;
+  const int64_t kp = (n_knots + n_wgs - 1) / n_wgs;
+  return kp <= 4 ? (int)kp : 0;
 }
 
 // Phase B, general form, for problem p (after phase A's flags are visible): any number of heads
@@ -738,11 +795,180 @@ __device__ inline void alloc_phase_b_mid(const AllocIO& io, int p, char* lds) {
   if (t == 0) io.status[p] = infeasible ? LUKV_ST_INFEASIBLE : 0;
 }
 
+// Phase B for a small problem (at most 1024 knots and 64 heads) by a workgroup of 1024 threads
+// with 32 KiB of LDS: one thread per knot; the hull segments that still offer units are compacted
+// into a list, and the threshold gain is found by ranking every such segment against all others
+// (a few hundred at most), which needs no digit passes.  Same result as the other forms.
+// What a thread of alloc_phase_b_small reads from global memory, so that a caller can issue the
+// loads early (they are cold: nothing else touches the curves) and run the phase later.
+struct AllocSmallLoad { int32_t vk, vv; float vc; int32_t lb, bm, n0, n_last; };
+
+__device__ __forceinline__ AllocSmallLoad alloc_small_load(const AllocIO& io, int p) {
+  const int NH = io.n_heads, Gp = io.n_grid, t = threadIdx.x;
+  const int64_t hbase = (int64_t)p * NH;
+  const bool mine = t < NH * Gp, head = t < NH;
+  const int32_t* kn = io.knots + hbase * Gp;
+  AllocSmallLoad ld;
+  ld.vk = mine ? kn[t] : 0;
+  ld.vc = mine ? io.curves[hbase * Gp + t] : 0.f;
+  ld.vv = mine ? io.vertex[hbase * Gp + t] : 0;
+  ld.lb = head ? io.b_min[hbase + t] : 0;
+  ld.bm = head ? io.b_max[hbase + t] : 0;
+  ld.n0 = head ? kn[(int64_t)t * Gp] : 0;
+  ld.n_last = head ? kn[(int64_t)t * Gp + Gp - 1] : 0;
+  return ld;
+}
+
+// budgets_lds (may be NULL): LDS array of n_heads budgets for the caller's own use;
+// write_out: whether this workgroup writes budgets and status to global memory (several
+// workgroups may run the same problem redundantly).
+__device__ inline void alloc_phase_b_small(const AllocIO& io, int p, char* lds, const AllocSmallLoad& pre,
+                                           int32_t* budgets_lds, bool write_out) {
+  const int NH = io.n_heads, Gp = io.n_grid, t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int64_t hbase = (int64_t)p * NH;
+  const int nseg = NH * Gp;
+  const int words = (Gp + 63) / 64;                       // NH * words <= 80
+  unsigned long long* l_mask = reinterpret_cast<unsigned long long*>(lds);           // [NH][words] <= 128
+  long long* red = reinterpret_cast<long long*>(lds + 1024);                         // sum b_min, units on offer, bad
+  unsigned long long* sel = reinterpret_cast<unsigned long long*>(lds + 1056);       // g*, units wanted at g*
+  unsigned* n_live = reinterpret_cast<unsigned*>(lds + 1072);
+  int32_t* l_lb = reinterpret_cast<int32_t*>(lds + 1088);                            // [64]
+  int32_t* l_cp = l_lb + 64;                                                         // [64]
+  unsigned long long* h_gt = reinterpret_cast<unsigned long long*>(lds + 1600);      // [64]
+  unsigned long long* h_eq = h_gt + 64;                                              // [64]
+  int32_t* l_kn = reinterpret_cast<int32_t*>(lds + 2624);                            // [1024]
+  float* l_cu = reinterpret_cast<float*>(lds + 6720);                                // [1024]
+  unsigned long long* live_key = reinterpret_cast<unsigned long long*>(lds + 10816); // [1024]
+  unsigned* live_w = reinterpret_cast<unsigned*>(lds + 19008);                       // [1024]
+  unsigned short* live_h = reinterpret_cast<unsigned short*>(lds + 23104);           // [1024] -> 25152
+  auto add = [](unsigned a, unsigned b) { return a + b; };
+  __syncthreads();
+  const bool mine = t < nseg, head = t < NH;
+  const int32_t vk = pre.vk, vv = pre.vv;
+  const float vc = pre.vc;
+  const long long lb = pre.lb, bm = pre.bm, n0 = pre.n0, n_last = pre.n_last;
+  if (t == 0) { red[0] = red[1] = red[2] = 0; sel[0] = 0ull; sel[1] = 0ull; *n_live = 0u; }
+  if (t < 128) l_mask[t] = 0ull;
+  if (t < 64) { h_gt[t] = 0ull; h_eq[t] = 0ull; }
+  __syncthreads();
+  const long long cp = bm < n_last ? bm : n_last;
+  if (head) { l_lb[t] = (int32_t)lb; l_cp[t] = (int32_t)cp; }
+  const int h = mine ? t / Gp : 0, g = mine ? t - h * Gp : 0;
+  if (mine) {
+    l_kn[t] = vk;
+    l_cu[t] = vc;
+    if (vv) atomicOr(&l_mask[h * words + (g >> 6)], 1ull << (g & 63));
+  }
+  // minimum retention and units on offer are sums over heads (the segments of a head tile
+  // (max(b_min, first knot), cap]): wave 0, 16-bit pieces cannot overflow a lane
+  if (wave == 0) {
+    const bool head_bad = head && (lb < 0 || lb > cp);
+    const long long from = lb > n0 ? lb : n0;
+    const unsigned offer = head && !head_bad && cp > from ? (unsigned)(cp - from) : 0u;
+    const unsigned keep = head && !head_bad ? (unsigned)lb : 0u;
+    const unsigned m_lo = wave_reduce_to_last(keep & 0xFFFFu, 0u, add), m_hi = wave_reduce_to_last(keep >> 16, 0u, add);
+    const unsigned w_lo = wave_reduce_to_last(offer & 0xFFFFu, 0u, add), w_hi = wave_reduce_to_last(offer >> 16, 0u, add);
+    const unsigned long long any_bad = __ballot(head_bad);
+    if (lane == 63) {
+      red[0] = (long long)(((unsigned long long)m_hi << 16) + m_lo);
+      red[1] = (long long)(((unsigned long long)w_hi << 16) + w_lo);
+      red[2] = any_bad ? 1 : 0;
+    }
+  }
+  __syncthreads();
+  // one segment per vertex (to the next vertex), clipped to (b_min, cap]; the live ones are listed
+  {
+    unsigned w = 0;
+    unsigned long long key = 0;
+    const unsigned long long* mk = l_mask + h * words;
+    if (mine && g < Gp - 1 && ((mk[g >> 6] >> (g & 63)) & 1ull)) {
+      int c = g + 1, wd = c >> 6;            // next vertex; the last knot is always one
+      unsigned long long m = mk[wd] & (~0ull << (c & 63));
+      while (m == 0ull && wd + 1 < words) m = mk[++wd];
+      c = m ? wd * 64 + __ffsll((long long)m) - 1 : Gp - 1;
+      const long long na = vk, nb = l_kn[h * Gp + c];
+      const double ua = (double)vc, ub = (double)l_cu[h * Gp + c];
+      const long long hlb = l_lb[h], hcp = l_cp[h];
+      const long long lo = max(na, hlb), hi = min(nb, hcp);
+      w = hi > lo ? (unsigned)(hi - lo) : 0u;
+      key = gain_key((ub - ua) / (double)(nb - na));
+    }
+    const unsigned long long live = __ballot(w != 0u);
+    if (live) {
+      unsigned at = 0;
+      const int leader = __ffsll((long long)live) - 1;
+      if (lane == leader) at = atomicAdd(n_live, (unsigned)__popcll(live));
+      at = (unsigned)__shfl((int)at, leader) + (unsigned)__popcll(live & ((1ull << lane) - 1ull));
+      if (w) { live_key[at] = key; live_w[at] = w; live_h[at] = (unsigned short)h; }
+    }
+  }
+  __syncthreads();
+  const long long R = io.B[p] - red[0];
+  const bool infeasible = red[2] != 0 || R < 0 || R > red[1];
+  const bool active = !infeasible && R > 0;
+  const int n = (int)*n_live;
+  // threshold gain g*: W(> g*) < R <= W(>= g*), by ranking each live segment against all; a
+  // power-of-two group of lanes shares one segment's ranking
+  if (active) {
+    int share = 1;
+    while (share < 64 && n * share * 2 <= 1024) share *= 2;
+    const int seg = t / share, sub = t % share;
+    const bool have = seg < n;
+    const unsigned long long me = have ? live_key[seg] : 0ull;
+    unsigned long long w_gt = 0, w_eq = 0;
+    if (have) {
+#pragma unroll 4
+      for (int j = sub; j < n; j += share) {
+        const unsigned long long kj = live_key[j];
+        const unsigned long long wj = live_w[j];
+        w_gt += kj > me ? wj : 0ull;
+        w_eq += kj == me ? wj : 0ull;
+      }
+    }
+    for (int o = 1; o < share; o <<= 1) {
+      w_gt += (unsigned long long)shfl_xor_i64((long long)w_gt, o);
+      w_eq += (unsigned long long)shfl_xor_i64((long long)w_eq, o);
+    }
+    if (have && sub == 0 && w_gt < (unsigned long long)R && (unsigned long long)R <= w_gt + w_eq) {
+      sel[0] = me;
+      sel[1] = (unsigned long long)R - w_gt;
+    }
+  }
+  __syncthreads();
+  const unsigned long long kstar = sel[0];
+  const long long rem = active ? (long long)sel[1] : 0;
+  if (active && t < n) {
+    const unsigned long long me = live_key[t];
+    if (me > kstar) atomicAdd(&h_gt[live_h[t]], (unsigned long long)live_w[t]);
+    else if (me == kstar) atomicAdd(&h_eq[live_h[t]], (unsigned long long)live_w[t]);
+  }
+  __syncthreads();
+  // budgets: everything above g*, the units at g* in head order
+  if (head) {
+    long long eq_before = 0;
+    for (int h2 = 0; h2 < t; ++h2) eq_before += (long long)h_eq[h2];
+    const long long eq = (long long)h_eq[t];
+    long long take = rem - eq_before;
+    take = take < 0 ? 0 : (take > eq ? eq : take);
+    const int32_t b = (int32_t)(lb + (active ? (long long)h_gt[t] + take : 0));
+    if (write_out) io.budgets[hbase + t] = b;
+    if (budgets_lds) budgets_lds[t] = b;
+  }
+  if (t == 0 && write_out) io.status[p] = infeasible ? LUKV_ST_INFEASIBLE : 0;
+}
+
+// whether alloc_phase_b_small takes the problem (by a workgroup of 1024 threads)
+__host__ __device__ inline bool alloc_small_ok(int n_heads, int n_grid) {
+  return n_heads <= 64 && n_heads * n_grid <= 1024;
+}
+
 // Phase B for problem p (after phase A's flags are visible); lds: scratch of lds_bytes, free
 // for this call.
 __device__ inline void alloc_phase_b(const AllocIO& io, int p, char* lds, int lds_bytes) {
   const int words = (io.n_grid + 63) / 64;
-  if (blockDim.x == 1024 && lds_bytes >= kAllocLdsBytes && io.n_heads <= 1024 && io.n_heads * words <= 1024)
+  if (blockDim.x == 1024 && lds_bytes >= 32768 && alloc_small_ok(io.n_heads, io.n_grid))
+    alloc_phase_b_small(io, p, lds, alloc_small_load(io, p), nullptr, true);
+  else if (blockDim.x == 1024 && lds_bytes >= kAllocLdsBytes && io.n_heads <= 1024 && io.n_heads * words <= 1024)
     alloc_phase_b_mid(io, p, lds);
   else
     alloc_phase_b_generic(io, p, lds, lds_bytes);

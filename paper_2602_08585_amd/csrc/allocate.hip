@@ -106,6 +106,11 @@ AllocIO make_alloc_io(int32_t n_problems, int32_t n_heads, int32_t n_grid, const
   return io;
 }
 
+void launch_allocate_vertices(const AllocIO& io, hipStream_t st) {
+  const int bpp = alloc_blocks_a(io.n_heads, io.n_grid);
+  hipLaunchKernelGGL(allocate_vertices_kernel, dim3(io.n_problems * bpp), dim3(256), 0, st, io, bpp);
+}
+
 int launch_allocate(const AllocIO& io, hipStream_t st) {
   const int bpp = alloc_blocks_a(io.n_heads, io.n_grid);
   hipLaunchKernelGGL(allocate_vertices_kernel, dim3(io.n_problems * bpp), dim3(256), 0, st, io, bpp);

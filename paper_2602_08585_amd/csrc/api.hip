@@ -38,20 +38,6 @@ static void* static_scratch_ptr() {
 static inline int64_t align_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
 static inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-// compute units of the current device (256 on MI355X), asked once
-static int cu_count() {
-  static int n = 0;
-  if (n == 0) {
-    int dev = 0, v = 0;
-    if (hipGetDevice(&dev) == hipSuccess &&
-        hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
-      n = v;
-    else
-      n = 256;
-  }
-  return n;
-}
-
 int validate_config(const lukv_config* cfg, HostCfg* out) {
   if (!cfg || !out || !cfg->cu_seqlens) return LUKV_EINVAL;
   if (cfg->dtype != LUKV_BF16 && cfg->dtype != LUKV_F32) return LUKV_EDTYPE;
@@ -109,22 +95,23 @@ int validate_config(const lukv_config* cfg, HostCfg* out) {
   // the kernels address one head's keys of one sequence with 32-bit byte offsets
   if ((int64_t)max_len * cfg->stride_tok * esize >= (1ll << 32)) return LUKV_EINVAL;
   out->max_len = max_len;
-  // keys per score workgroup: at most 64 chunks per head (pass B merges them in its prologue)
+  // Keys per score workgroup: a multiple of every sequence's granule of softmax statistics (512
+  // keys, doubled until the sequence has at most 64 granules).  Calls with many workgroups
+  // (several layers, long batches) take longer chunks: the prologue of a score workgroup (queries,
+  // first tile, merge of the granules' statistics) is then paid once per 1024 or 2048 keys.  The
+  // thresholds are in units of the 512 workgroups a 256-unit chip holds at once, from timings at
+  // 1 to 32 layers of 32k context; they are constants, so that the chunking - which never
+  // changes a result - is a function of the configuration alone.
   g.chunk_keys = 512;
   while ((max_len + g.chunk_keys - 1) / g.chunk_keys > 64) g.chunk_keys *= 2;
-  // Calls with many workgroups (several layers, long batches) take longer chunks: the prologue of
-  // a score workgroup (queries, first tile, merge of the per-chunk pairs) is then paid once per
-  // 1024 or 2048 keys.  Thresholds in units of the workgroups the chip holds at once (two per
-  // CU), from timings at 1 to 32 layers of 32k context.
   {
-    const int64_t slots = 2 * (int64_t)cu_count();
     auto n_wgs = [&](int chunk) {
       int64_t n = 0;
       for (int s = 0; s < cfg->n_seqs; ++s) n += (out->seq.cu[s + 1] - out->seq.cu[s] + chunk - 1) / chunk;
       return n * g.n_kv_heads * g.n_layers;
     };
-    if (g.chunk_keys < 1024 && n_wgs(1024) >= 2 * slots) g.chunk_keys = 1024;
-    if (g.chunk_keys == 1024 && n_wgs(2048) >= 4 * slots) g.chunk_keys = 2048;
+    if (g.chunk_keys < 1024 && n_wgs(1024) >= 1024) g.chunk_keys = 1024;
+    if (g.chunk_keys == 1024 && n_wgs(2048) >= 2048) g.chunk_keys = 2048;
   }
   out->n_hi = cfg->n_seqs * g.n_layers * g.n_kv_heads;
   return LUKV_OK;
@@ -153,7 +140,7 @@ WsLayout make_layout(const HostCfg& hc, int32_t n_grid, bool alloc_only) {
   auto take = [&](int64_t bytes) { const int64_t o = off; off = align_up(off + bytes, 256); return o; };
   const int64_t n_sel = alloc_only ? 0 : w.n_hi;
   w.hist = take(n_sel * w.max_slices * (kHistBins / 2) * 4);
-  w.partial = take((int64_t)w.n_hi * w.max_chunks * w.rows_padded * 8);
+  w.partial = take((int64_t)w.n_hi * 64 * w.rows_padded * 4);   // one log-sum per (granule of keys, row)
   const int64_t score_bytes = (int64_t)g.n_layers * g.n_kv_heads * g.total_tokens * 4;
   w.raw = take(score_bytes);
   w.pooled = take(score_bytes);
@@ -167,6 +154,9 @@ WsLayout make_layout(const HostCfg& hc, int32_t n_grid, bool alloc_only) {
   w.alloc_vertex = take(nseg * 4);
   w.seg_key = take(nseg * 8);
   w.seg_w = take(nseg * 4);
+  w.keepmask = take(n_sel * 1024 * 4);
+  w.runpre = take(n_sel * 1032 * 4);
+  w.head_flag = take(n_sel * 4);
   w.total = off;
   return w;
 }
@@ -219,7 +209,7 @@ static int score_impl(const lukv_config* cfg, const void* q_win, const void* k, 
   const WsLayout lay = make_layout(hc, 0, false);
   if ((rc = check_ws(lay, ws, ws_bytes))) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  if ((rc = launch_score_raw(hc, lay, q_win, k, lse, nullptr, (char*)ws, st))) return rc;
+  if ((rc = launch_score_raw(hc, lay, q_win, k, lse, nullptr, false, (char*)ws, st))) return rc;
   return launch_pool(hc, lay, pooled, (char*)ws, st);
 }
 
@@ -298,17 +288,26 @@ static int evict_impl(const lukv_config* cfg, const void* q_win, const void* k, 
   if ((rc = check_ws(lay, ws, ws_bytes))) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
   char* w = (char*)ws;
-  float* scores = pooled ? pooled : reinterpret_cast<float*>(w + lay.pooled);
+  // the whole-head selection keeps the pooled scores in registers: they are only written out when
+  // the caller asks for them
+  float* scores = pooled ? pooled : (select_whole_head(hc) ? nullptr : reinterpret_cast<float*>(w + lay.pooled));
   int32_t* sel_status = status + cfg->n_seqs;
   // the allocation never looks at scores: its two phases ride along as a few extra workgroups
-  // of the second score kernel and of the first selection kernel (where they do not displace
-  // resident scoring workgroups); selection pools the raw metric on the fly
+  // of the two score kernels (where they do not displace resident scoring workgroups), so the
+  // budgets are there when the selection starts; selection pools the raw metric on the fly
   const int n_heads = hc.g.n_layers * hc.g.n_kv_heads;
   const AllocIO aio = make_alloc_io(cfg->n_seqs, n_heads, n_grid, curves, knots, b_min, b_max, B_total,
                                     budgets, offsets, status, lay, w);
-  if ((rc = launch_score_raw(hc, lay, q_win, k, lse, &aio, w, st))) return rc;
-  rc = launch_select_compact(hc, lay, &aio, reinterpret_cast<const float*>(w + lay.raw), true, scores, budgets,
-                             offsets, true, k, v, kept_idx, k_out, v_out, out_rows, sel_status, w, st);
+  // Where the budget phase runs: with the whole-head selection, inside the head workgroups when
+  // the call holds one small allocation problem, else as extra workgroups of the accumulation
+  // kernel; with the per-slice selection, as extra workgroups of its first kernel.
+  const bool whole = select_whole_head(hc);
+  const bool b_in_head = whole && cfg->n_seqs == 1 && alloc_small_ok(n_heads, n_grid);
+  const bool b_in_accum = whole && !b_in_head;
+  if ((rc = launch_score_raw(hc, lay, q_win, k, lse, &aio, b_in_accum, w, st))) return rc;
+  rc = launch_select_compact(hc, lay, b_in_accum ? nullptr : &aio, reinterpret_cast<const float*>(w + lay.raw), true,
+                             scores, budgets, offsets, true, k, v, kept_idx, k_out, v_out, out_rows, sel_status,
+                             w, st);
   return rc;
 }
 
@@ -439,8 +438,8 @@ int lukv_evict_budgets(const lukv_config* cfg, const void* q_win, const void* k,
   if ((rc = check_ws(lay, ws, ws_bytes))) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
   char* w = (char*)ws;
-  float* scores = pooled ? pooled : reinterpret_cast<float*>(w + lay.pooled);
-  if ((rc = launch_score_raw(hc, lay, q_win, k, lse, nullptr, w, st))) return rc;
+  float* scores = pooled ? pooled : (select_whole_head(hc) ? nullptr : reinterpret_cast<float*>(w + lay.pooled));
+  if ((rc = launch_score_raw(hc, lay, q_win, k, lse, nullptr, false, w, st))) return rc;
   rc = launch_select_compact(hc, lay, nullptr, reinterpret_cast<const float*>(w + lay.raw), true, scores, budgets,
                              const_cast<int64_t*>(offsets), false, k, v, kept_idx, k_out, v_out, out_rows,
                              status, w, st);

@@ -57,7 +57,7 @@ int lukv_set_stage_events(void* const* events, int32_t n_events) {
 
 const char* lukv_stage_name(int32_t stage) {
   static const char* const names[kNumStages] = {
-      "allocate", "score_stats", "score_accum", "pool", "sel_hist", "sel_tail", "sel_emit"};
+      "allocate", "score_stats", "score_accum", "pool", "sel_hist", "sel_tail", "sel_emit", "sel_head", "sel_gather"};
   return stage >= 0 && stage < kNumStages ? names[stage] : "";
 }
 

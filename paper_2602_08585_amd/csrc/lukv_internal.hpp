@@ -52,13 +52,16 @@ struct WsLayout {
   int64_t head_dig;              // uint2 [n_hi] first digit of the selection: (base key, shift)
   int64_t by_bin;                // u64 [n_layers * n_kv_heads * total_tokens] (key, position) by slice and bin
   int64_t cand;                  // u64, same shape: threshold candidates of a head beyond the LDS list
-  int64_t partial;               // float2 [n_hi * max_chunks * rows_padded]
+  int64_t partial;               // float [n_hi * 64 * rows_padded] log-sum of every (granule of keys, row)
   int64_t raw;                   // float [n_layers * n_kv_heads * total_tokens]
   int64_t pooled;                // float, same shape
   int64_t sel_state;             // uint4 [n_hi]
   int64_t slice_cnt;             // uint2 [n_hi * max_slices] kept rows / ties before each slice
   int64_t seg_key;               // u64 [n_problems * n_heads * n_grid]
   int64_t seg_w;                 // u32 [n_problems * n_heads * n_grid]
+  int64_t keepmask;              // u32 [n_hi * 1024] whole-head selection: keep bits of every 32-position run
+  int64_t runpre;                // u32 [n_hi * 1032] kept rows before every run (entry 1024: the head's total)
+  int64_t head_flag;             // u32 [n_hi] status bits a head raised
   int64_t total;
   int32_t n_hi, max_chunks, max_slices, range_stride, rows_padded;
 };
@@ -77,10 +80,11 @@ SeqTab tiles_for(const SeqTab& seq, int tile, int shrink);  // tiles over (L_s -
 // Launchers (enqueue only; return a LUKV_* code).
 struct AllocIO;
 // raw (unpooled) metric into the workspace; aio != NULL: the allocation's first phase rides
-// along in the second score kernel
+// along in the score kernels, and its second phase too if b_in_accum (budgets and status are then
+// complete when the second kernel ends; otherwise the selection carries it)
 // lse != NULL: the window rows' log-sum-exp is given, pass A is not launched
 int launch_score_raw(const HostCfg& hc, const WsLayout& lay, const void* q, const void* k,
-                     const float* lse, const AllocIO* aio, char* ws, hipStream_t st);
+                     const float* lse, const AllocIO* aio, bool b_in_accum, char* ws, hipStream_t st);
 int launch_pool(const HostCfg& hc, const WsLayout& lay, float* pooled_out, char* ws, hipStream_t st);
 // aio != NULL: the allocation's second phase rides along in the first selection kernel
 int launch_select_compact(const HostCfg& hc, const WsLayout& lay, const AllocIO* aio,
@@ -88,11 +92,14 @@ int launch_select_compact(const HostCfg& hc, const WsLayout& lay, const AllocIO*
                           float* pooled_out, const int32_t* budgets, int64_t* offsets,
                           bool make_offsets, const void* k, const void* v, int32_t* kept_idx, void* k_out, void* v_out,
                           int64_t out_rows, int32_t* status, char* ws, hipStream_t st);
+// every sequence short enough for the whole-head form of the selection (scores of a head in LDS)
+bool select_whole_head(const HostCfg& hc);
 AllocIO make_alloc_io(int32_t n_problems, int32_t n_heads, int32_t n_grid, const float* curves,
                       const int32_t* knots, const int32_t* b_min, const int32_t* b_max,
                       const int64_t* B_total, int32_t* budgets, int64_t* offsets, int32_t* status,
                       const WsLayout& lay, char* ws);
 int launch_allocate(const AllocIO& io, hipStream_t st);
+void launch_allocate_vertices(const AllocIO& io, hipStream_t st);   // first phase only
 // static profile (Eq. 11): io0 describes the calibration queries as allocation problems whose
 // budgets / status arrays are scratch; rho is a host array
 int launch_profile_build(const AllocIO& io0, int32_t L, int32_t n_rho, const double* rho, float* phi,
@@ -112,7 +119,7 @@ int launch_decode(const HostCfg& hc, const void* q, const void* kp, const void* 
 
 // Optional instrumentation (lukv_set_stage_events): the main kernel of a stage is launched with
 // the caller's start / stop events attached to its own dispatch.
-enum Stage { kStAllocate = 0, kStStats, kStAccum, kStPool, kStHist, kStTail, kStEmit, kNumStages };
+enum Stage { kStAllocate = 0, kStStats, kStAccum, kStPool, kStHist, kStTail, kStEmit, kStHead, kStGather, kNumStages };
 void stage_events(int stage, hipEvent_t* start, hipEvent_t* stop);   // NULLs when none are set
 
 template <class... KArgs, class... Args>

@@ -24,14 +24,15 @@
 // "half hf = l/32 owns elements [hf*D/2, (hf+1)*D/2) of the row", so any internal ordering
 // of k is the same on both sides.  Output: acc[v] is row 8*(v/4) + 4*(l/32) + v%4, column l%32.
 //
-// When the fused path asks for it, the first blockIdx.x values of the second kernel run the
-// first phase of the budget allocation instead of scoring (it does not depend on scores).
+// When the fused path asks for it, the first blockIdx.x values of the two kernels run the two
+// phases of the budget allocation instead of scoring (it does not depend on scores).
 #include <string.h>
 
 #include <type_traits>
 
 #include "alloc_device.hpp"
 #include "lukv_internal.hpp"
+
 
 namespace lukv {
 
@@ -165,18 +166,48 @@ __device__ __forceinline__ void merge_stats(float& m, float& z, float m2, float 
   m = mm;
 }
 
+// Keys per granule of softmax statistics for a sequence of L keys: 512, doubled until there are
+// at most kMaxGranules granules.  Chunks of keys (what a workgroup streams) are multiples of it.
+constexpr int kMaxGranules = 64;
+__host__ __device__ inline int granule_keys(int L) {
+  int gkeys = 512;
+  while ((L + gkeys - 1) / gkeys > kMaxGranules) gkeys *= 2;
+  return gkeys;
+}
+
+// Knot of the allocation's first phase that this wave takes in the spread form (-1: none).
+// Scoring workgroups are numbered over the whole grid; workgroup b owns knots [b*kp, (b+1)*kp),
+// one per wave.
+__device__ __forceinline__ int64_t spread_item(const AllocIO& aio, int kp, int n_front_blocks) {
+  if (kp <= 0) return -1;
+  const int64_t n_x = (int64_t)gridDim.x - n_front_blocks;
+  const int64_t b = ((int64_t)blockIdx.z * gridDim.y + blockIdx.y) * n_x + ((int64_t)blockIdx.x - n_front_blocks);
+  const int wave = threadIdx.x >> 6;
+  const int64_t item = b * kp + wave;
+  const int64_t n_knots = (int64_t)aio.n_problems * aio.n_heads * aio.n_grid;
+  return (wave < kp && item < n_knots) ? item : -1;
+}
+
 // ---- pass A: softmax statistics ----------------------------------------------------------
 template <bool F32, int D, int NBM, int RG>
-__global__ __launch_bounds__(256, (F32 && D == 128) ? 1 : 2) void score_stats_kernel(Geom g, SeqTab tab, const char* q,
-                                                          const char* k, float2* partial,
-                                                          int max_chunks, int rows_padded) {
+__global__ __launch_bounds__(256, (F32 && D == 128) ? 1 : 2) void score_stats_kernel(Geom g, SeqTab tab, AllocIO aio,
+                                                          int n_alloc_blocks, int alloc_bpp, int alloc_spread,
+                                                          const char* q,
+                                                          const char* k, float* lpart,
+                                                          int rows_padded) {
   using T = Tile<F32, D, RG>;
   constexpr int kBufRows = T::kKeys > 32 * NBM ? T::kKeys : 32 * NBM;   // K tile or one Q row group
   __shared__ u32x4 ktile[kBufRows * T::kLdsRowU4];
   __shared__ float2 wstat[4][NBM][32];
 
+  if ((int)blockIdx.x < n_alloc_blocks) {
+    // a few short extra workgroups: hull vertices of the budget allocation (no use of scores)
+    if (blockIdx.y == 0 && blockIdx.z == 0 && (int)blockIdx.x / alloc_bpp < aio.n_problems)
+      alloc_phase_a(aio, blockIdx.x / alloc_bpp, blockIdx.x % alloc_bpp);
+    return;
+  }
   int seq, ch;
-  find_tile(tab, blockIdx.x, seq, ch);
+  find_tile(tab, blockIdx.x - n_alloc_blocks, seq, ch);
   const int kvh = blockIdx.y, layer = blockIdx.z;
   const int tok0 = tab.cu[seq], L = tab.cu[seq + 1] - tok0, P = L - g.window;
   const int hi = (seq * g.n_layers + layer) * g.n_kv_heads + kvh;
@@ -191,6 +222,12 @@ __global__ __launch_bounds__(256, (F32 && D == 128) ? 1 : 2) void score_stats_ke
   const char* kbase = k + ((int64_t)layer * g.sl + (int64_t)kvh * g.sh + (int64_t)tok0 * g.st) * T::kEsize;
   const int j_begin = ch * g.chunk_keys;
   const int j_end = min(L, j_begin + g.chunk_keys);
+  // Spread form of the allocation's first phase: this workgroup takes up to four knots, one per
+  // wave.  Their loads are issued ahead of the K tile's and consumed after the queries are on
+  // their way, so the divisions run while the tile is in flight.
+  const int64_t a_item = spread_item(aio, alloc_spread, n_alloc_blocks);
+  AllocKnotLoad a_ld;
+  if (a_item >= 0) a_ld = alloc_knot_load(aio, a_item);
   // byte offsets inside one head's keys fit 32 bits (checked on the host)
   const unsigned tok_bytes = (unsigned)(g.st * T::kEsize);
   const int ld_row0 = T::kPrivate ? 32 * (int)(threadIdx.x >> 6) + (int)(threadIdx.x & 63) / T::kRowU4
@@ -200,20 +237,24 @@ __global__ __launch_bounds__(256, (F32 && D == 128) ? 1 : 2) void score_stats_ke
   const unsigned ld_stride = (unsigned)T::kLoadRowStep * tok_bytes, ld_tile = (unsigned)T::kKeys * tok_bytes;
   const unsigned ld_last = (unsigned)(L - 1) * tok_bytes + (unsigned)ld_col * 16u;
   unsigned ld_off = (unsigned)(j_begin + ld_row0) * tok_bytes + (unsigned)ld_col * 16u;
+  // the window queries of the first row group are requested ahead of the first K tile (they come
+  // from L2 and are parked and picked up while the tile is still on its way from HBM)
   u32x4 pre[T::kLoads];
-  k_issue<F32, D, RG, T::kLoads>(pre, kbase, ld_off, ld_stride, ld_last);
-
   u32x4 qreg[NBM][T::kHalfU4];
   {
     u32x4 qtmp[QStage<F32, D, NBM>::kLoads];
+    q_fetch<F32, D, NBM, QStage<F32, D, NBM>::kLoads>(qtmp, g, q, layer, kvh, seq, 0);
+    k_issue<F32, D, RG, T::kLoads>(pre, kbase, ld_off, ld_stride, ld_last);
     for (int grp = 0; grp < RG; ++grp) {
-      q_fetch<F32, D, NBM, QStage<F32, D, NBM>::kLoads>(qtmp, g, q, layer, kvh, seq, grp);
+      if (grp) q_fetch<F32, D, NBM, QStage<F32, D, NBM>::kLoads>(qtmp, g, q, layer, kvh, seq, grp);
       if (grp) __syncthreads();
       q_park<F32, D, NBM, QStage<F32, D, NBM>::kLoads>(qtmp, ktile);
       __syncthreads();
       if (rg == grp) q_pick<F32, D, NBM, T::kHalfU4>(qreg, ktile, lane);
     }
   }
+  // the allocation's knot of this wave: its loads are older than the queries', so they are back
+  if (a_item >= 0) alloc_knot_finish(aio, a_item, a_ld);
   __syncthreads();   // the buffer now turns into the K tile
 
   // window row index of this lane's query in every block (for the causal range)
@@ -224,6 +265,36 @@ __global__ __launch_bounds__(256, (F32 && D == 128) ? 1 : 2) void score_stats_ke
   float m[NBM], z[NBM];
 #pragma unroll
   for (int nb = 0; nb < NBM; ++nb) { m[nb] = -INFINITY; z[nb] = 0.f; }
+
+  // Statistics are published per granule of keys, a function of the sequence length alone (512
+  // keys, doubled until a sequence has at most 64 granules), whatever chunk the call shape gives
+  // a workgroup: the merged constant of a row, and with it every score, is then bitwise the same
+  // for a layer scored alone or inside a larger call.  Published value: log2 of the granule's
+  // sum of exponentials, l = max * a + log2(sum).
+  const int gran = granule_keys(L);
+  auto publish = [&](int gidx) {
+    // lane l and l^32 hold the same query rows over different keys
+#pragma unroll
+    for (int nb = 0; nb < NBM; ++nb) {
+      const float m2 = __shfl_xor(m[nb], 32), z2 = __shfl_xor(z[nb], 32);
+      merge_stats(m[nb], z[nb], m2, z2, a);
+      if (lane < 32) wstat[wave][nb][lane] = make_float2(m[nb], z[nb]);
+      m[nb] = -INFINITY;
+      z[nb] = 0.f;
+    }
+    __syncthreads();
+    // merge the key subtiles of every row group
+    for (int r = threadIdx.x; r < rows_padded; r += 256) {
+      const int blk = r >> 5, grp = blk / g.blocks_per_group, nb = blk - grp * g.blocks_per_group;
+      float mm = -INFINITY, zz = 0.f;
+      for (int t = 0; t < n_kt; ++t) {
+        const float2 st = wstat[grp * n_kt + t][nb][r & 31];
+        merge_stats(mm, zz, st.x, st.y, a);
+      }
+      lpart[((int64_t)hi * kMaxGranules + gidx) * rows_padded + r] = mm == -INFINITY ? -INFINITY : fmaf(mm, a, log2f(zz));
+    }
+    __syncthreads();   // wstat is rewritten by the next granule
+  };
 
   for (int j0 = j_begin; j0 < j_end; j0 += T::kKeys) {
     tile_sync<T::kPrivate>();      // the previous tile has been read
@@ -268,50 +339,49 @@ __global__ __launch_bounds__(256, (F32 && D == 128) ? 1 : 2) void score_stats_ke
           }
         }
       };
-      if (jw + 32 > P) fold(std::true_type{}); else fold(std::false_type{});
+      if (jw + 32 > P) {
+        fold(std::true_type{});
+      } else {
+        fold(std::false_type{});
+      }
     }
-  }
-
-  // lane l and l^32 hold the same query rows over different keys
-#pragma unroll
-  for (int nb = 0; nb < NBM; ++nb) {
-    const float m2 = __shfl_xor(m[nb], 32), z2 = __shfl_xor(z[nb], 32);
-    merge_stats(m[nb], z[nb], m2, z2, a);
-    if (lane < 32) wstat[wave][nb][lane] = make_float2(m[nb], z[nb]);
-  }
-  __syncthreads();
-  // merge the key subtiles of every row group and publish this chunk's pair per row
-  for (int r = threadIdx.x; r < rows_padded; r += 256) {
-    const int blk = r >> 5, grp = blk / g.blocks_per_group, nb = blk - grp * g.blocks_per_group;
-    float mm = -INFINITY, zz = 0.f;
-    for (int t = 0; t < n_kt; ++t) {
-      const float2 st = wstat[grp * n_kt + t][nb][r & 31];
-      merge_stats(mm, zz, st.x, st.y, a);
-    }
-    partial[((int64_t)hi * max_chunks + ch) * rows_padded + r] = make_float2(mm, zz);
+    const int j_next = j0 + T::kKeys;
+    if (j_next >= j_end || j_next % gran == 0) publish((j_next - 1) / gran);   // uniform over the workgroup
   }
 }
 
 // ---- pass B: normalised window sums ------------------------------------------------------
 template <bool F32, int D, int NBM, int RG>
 __global__ __launch_bounds__(256, (F32 && D == 128) ? 1 : 2) void score_accum_kernel(Geom g, SeqTab tab, AllocIO aio,
-                                                          int n_alloc_blocks, int alloc_bpp,
+                                                          int n_alloc_blocks, int alloc_bpp, int alloc_spread,
                                                           const char* q,
-                                                          const char* k, const float2* partial,
+                                                          const char* k, const float* lpart,
                                                           const float* lse,
                                                           float* raw, float2* range, int max_chunks,
                                                           int rows_padded) {
   using T = Tile<F32, D, RG>;
   constexpr int kBufRows = T::kKeys > 32 * NBM ? T::kKeys : 32 * NBM;   // K tile or one Q row group
-  __shared__ u32x4 ktile[kBufRows * T::kLdsRowU4];
+  // (at least 32 KiB: the buffer is also the scratch of the allocation's budget phase)
+  constexpr int kBufU4 = kBufRows * T::kLdsRowU4 > 2048 ? kBufRows * T::kLdsRowU4 : 2048;
+  __shared__ u32x4 ktile[kBufU4];
   __shared__ __align__(16) float rowc_s[kMaxRows];
-  __shared__ float2 pm[kMaxRows];
+  __shared__ float2 pm[1024];
   __shared__ float colred[4][32];
 
   if ((int)blockIdx.x < n_alloc_blocks) {
-    // a few short extra workgroups: hull vertices of the budget allocation (no use of scores)
-    if (blockIdx.y == 0 && blockIdx.z == 0 && (int)blockIdx.x / alloc_bpp < aio.n_problems)
-      alloc_phase_a(aio, blockIdx.x / alloc_bpp, blockIdx.x % alloc_bpp);
+    // Extra workgroups, dispatched first (no use of scores).  alloc_bpp == 0: one per allocation
+    // problem, the budgets (the hull vertices are there since the previous kernel; the K-tile
+    // buffer is the scratch).  alloc_bpp > 0: the hull vertices, when there is no statistics
+    // kernel to carry them.
+    static_assert(sizeof(ktile) >= 32768, "the budget phase needs 32 KiB of LDS");
+    if (blockIdx.y == 0 && blockIdx.z == 0) {
+      if (alloc_bpp == 0) {
+        if ((int)blockIdx.x < aio.n_problems)
+          alloc_phase_b(aio, blockIdx.x, reinterpret_cast<char*>(ktile), (int)sizeof(ktile));
+      } else if ((int)blockIdx.x / alloc_bpp < aio.n_problems) {
+        alloc_phase_a(aio, blockIdx.x / alloc_bpp, blockIdx.x % alloc_bpp);
+      }
+    }
     return;
   }
   int seq, ch;
@@ -330,6 +400,9 @@ __global__ __launch_bounds__(256, (F32 && D == 128) ? 1 : 2) void score_accum_ke
   const char* kbase = k + ((int64_t)layer * g.sl + (int64_t)kvh * g.sh + (int64_t)tok0 * g.st) * T::kEsize;
   const int j_begin = ch * g.chunk_keys;
   const int j_end = min(P, j_begin + g.chunk_keys);
+  // spread form of the allocation's first phase (only when no statistics kernel carries it)
+  const int64_t a_item = spread_item(aio, alloc_spread, n_alloc_blocks);
+  if (a_item >= 0) alloc_knot_finish(aio, a_item, alloc_knot_load(aio, a_item));
   // byte offsets inside one head's keys fit 32 bits (checked on the host)
   const unsigned tok_bytes = (unsigned)(g.st * T::kEsize);
   const int ld_row0 = T::kPrivate ? 32 * (int)(threadIdx.x >> 6) + (int)(threadIdx.x & 63) / T::kRowU4
@@ -343,20 +416,21 @@ __global__ __launch_bounds__(256, (F32 && D == 128) ? 1 : 2) void score_accum_ke
   const int n_tiles = j_end > j_begin ? (j_end - j_begin + T::kKeys - 1) / T::kKeys : 0;
   const int j_first = j_begin + (n_tiles > 0 ? n_tiles - 1 : 0) * T::kKeys;
   unsigned ld_off = (unsigned)(j_first + ld_row0) * tok_bytes + (unsigned)ld_col * 16u;
+  // Requests go out in the order their answers are needed, since a wave sees its loads return
+  // in order: the window queries of the first row group and the first batch of pass A's
+  // statistics (both from L2), then the first K tile (from HBM, the long wait), so the queries
+  // are parked and the softmax constants merged while that tile is on its way.
   u32x4 pre[T::kLoads];
-  k_issue<F32, D, RG, T::kLoads>(pre, kbase, ld_off, ld_stride, ld_last);
-
-  // window queries of the first row group: in flight together with the K tile above and the
-  // per-chunk statistics below
   u32x4 qtmp[QStage<F32, D, NBM>::kLoads];
   q_fetch<F32, D, NBM, QStage<F32, D, NBM>::kLoads>(qtmp, g, q, layer, kvh, seq, 0);
 
   // Softmax constant of every window row, c_r = log2 of the row's denominator.  Either the
   // caller's log-sum-exp (row r = query head r / w of the group, window row r % w), or the merge
-  // of the (max, sum) pairs that pass A left per chunk of this head, c_r = max_r * a + log2(sum_r):
-  // each thread folds a share of the chunks of one row, 32 pairs in flight at once; LDS joins
-  // the shares.
+  // of the granules' log-sums l that pass A left, c_r = M + log2(sum exp2(l - M)), M = max l:
+  // a thread takes four rows (one 16-byte load per granule) and every (256 / (rows / 4))-th
+  // granule, eight loads in flight at a time; LDS joins the threads that share rows.
   if (lse) {
+    k_issue<F32, D, RG, T::kLoads>(pre, kbase, ld_off, ld_stride, ld_last);
     const int64_t qh0 = (int64_t)layer * g.n_q_heads + (int64_t)kvh * g.group;
     const int64_t row_len = (int64_t)tab.n_seqs * g.window;
     for (int r = threadIdx.x; r < kMaxRows; r += 256) {
@@ -365,42 +439,56 @@ __global__ __launch_bounds__(256, (F32 && D == 128) ? 1 : 2) void score_accum_ke
       rowc_s[r] = c;
     }
   } else {
-    const int n_chunks = (L + g.chunk_keys - 1) / g.chunk_keys;   // chunks pass A used
-    const int nparts = rows_padded >= 256 ? 1 : 256 / rows_padded;
-    const int cpp = (n_chunks + nparts - 1) / nparts;
-    const float2* hp = partial + (int64_t)hi * max_chunks * rows_padded;
-    for (int item = threadIdx.x; item < rows_padded * nparts; item += 256) {
-      const int r = item % rows_padded, part = item / rows_padded;
-      const int c_end = min(n_chunks, (part + 1) * cpp);
-      float mm = -INFINITY, zz = 0.f;
-      for (int c0 = part * cpp; c0 < c_end; c0 += 32) {
-        float2 st[32];
+    const int n_gran = (L + granule_keys(L) - 1) / granule_keys(L);
+    const int tpr = rows_padded >> 2;                 // threads that cover the rows once: 8 .. 128
+    const int groups = 256 / tpr;                     // 2 .. 32
+    const int col = (int)threadIdx.x % tpr, grp0 = (int)threadIdx.x / tpr;
+    const float* hp = lpart + (int64_t)hi * kMaxGranules * rows_padded + 4 * col;
+    float pmax[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY}, psum[4] = {0.f, 0.f, 0.f, 0.f};
+    f32x4 v[8];
+    auto fetch8 = [&](int g0) {
 #pragma unroll
-        for (int u = 0; u < 32; ++u)
-          st[u] = c0 + u < c_end ? hp[(int64_t)(c0 + u) * rows_padded + r] : make_float2(-INFINITY, 0.f);
-        float rm = -INFINITY;
-#pragma unroll
-        for (int u = 0; u < 32; ++u) rm = fmaxf(rm, st[u].x);
-        const float rms = rm == -INFINITY ? 0.f : rm;
-        float rz = 0.f;
-#pragma unroll
-        for (int u = 0; u < 32; ++u) rz = fmaf(st[u].y, fast_exp2((st[u].x - rms) * a), rz);
-        merge_stats(mm, zz, rm, rz, a);
+      for (int u = 0; u < 8; ++u) {
+        const int gi = g0 + u * groups;
+        v[u] = gi < n_gran ? *reinterpret_cast<const f32x4*>(hp + (int64_t)gi * rows_padded)
+                           : f32x4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
       }
-      if (nparts == 1) rowc_s[r] = r < g.rows ? mm * a + log2f(zz) : INFINITY;
-      else pm[part * rows_padded + r] = make_float2(mm, zz);
+    };
+    int g0 = grp0 < groups ? grp0 : n_gran;           // (threads beyond the last group idle)
+    fetch8(g0);
+    k_issue<F32, D, RG, T::kLoads>(pre, kbase, ld_off, ld_stride, ld_last);
+    while (g0 < n_gran) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        float bm = pmax[e];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) bm = fmaxf(bm, v[u][e]);
+        const float ref = bm == -INFINITY ? 0.f : bm;
+        float bs = psum[e] * fast_exp2(pmax[e] - ref);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) bs += fast_exp2(v[u][e] - ref);
+        pmax[e] = bm;
+        psum[e] = bs;
+      }
+      g0 += 8 * groups;
+      if (g0 < n_gran) fetch8(g0);
     }
-    if (nparts > 1) {
-      __syncthreads();
-      for (int r = threadIdx.x; r < rows_padded; r += 256) {
-        float mm = -INFINITY, zz = 0.f;
-        for (int part = 0; part < nparts; ++part) {
-          const float2 st = pm[part * rows_padded + r];
-          merge_stats(mm, zz, st.x, st.y, a);
-        }
-        // padded rows never contribute: +inf makes exp2(S*a - c) vanish
-        rowc_s[r] = r < g.rows ? mm * a + log2f(zz) : INFINITY;
+    if (grp0 < groups) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) pm[grp0 * rows_padded + 4 * col + e] = make_float2(pmax[e], psum[e]);
+    }
+    __syncthreads();
+    for (int r = threadIdx.x; r < rows_padded; r += 256) {
+      float bm = -INFINITY;
+      for (int p2 = 0; p2 < groups; ++p2) bm = fmaxf(bm, pm[p2 * rows_padded + r].x);
+      const float ref = bm == -INFINITY ? 0.f : bm;
+      float bs = 0.f;
+      for (int p2 = 0; p2 < groups; ++p2) {
+        const float2 st = pm[p2 * rows_padded + r];
+        bs = fmaf(st.y, fast_exp2(st.x - ref), bs);
       }
+      // padded rows never contribute: +inf makes exp2(S*a - c) vanish
+      rowc_s[r] = r < g.rows ? bm + log2f(bs) : INFINITY;
     }
     for (int r = rows_padded + threadIdx.x; r < kMaxRows; r += 256) rowc_s[r] = INFINITY;
   }
@@ -530,48 +618,74 @@ __global__ __launch_bounds__(256) void pool_kernel(Geom g, SeqTab tab, const flo
 // ---- launchers ---------------------------------------------------------------------------
 template <bool F32, int D, int NBM, int RG>
 static int launch_raw_t(const HostCfg& hc, const WsLayout& lay, const void* q, const void* k,
-                        const float* lse, const AllocIO* aio, char* ws, hipStream_t st) {
+                        const float* lse, const AllocIO* aio, bool b_in_accum, char* ws, hipStream_t st) {
   const Geom& g = hc.g;
-  float2* partial = reinterpret_cast<float2*>(ws + lay.partial);
+  float* lpart = reinterpret_cast<float*>(ws + lay.partial);
   float* raw = reinterpret_cast<float*>(ws + lay.raw);
   float2* range = reinterpret_cast<float2*>(ws + lay.range);
   const SeqTab tabA = tiles_for(hc.seq, g.chunk_keys, 0);
   const SeqTab tabB = tiles_for(hc.seq, g.chunk_keys, g.window);
   AllocIO io;
   memset(&io, 0, sizeof(io));
-  int n_alloc = 0, bpp = 1;
-  // the extra blocks are padded to a multiple of 8 so that a chunk lands on the same XCD (and
-  // its L2) in both passes
-  if (aio) { io = *aio; bpp = alloc_blocks_a(aio->n_heads, aio->n_grid); n_alloc = (aio->n_problems * bpp + 7) / 8 * 8; }
-  dim3 gridA(tabA.tile0[tabA.n_seqs], g.n_kv_heads, g.n_layers);
-  dim3 gridB(tabB.tile0[tabB.n_seqs] + n_alloc, g.n_kv_heads, g.n_layers);
+  // The allocation never looks at scores, so it rides in the score kernels.  First phase (hull
+  // vertices): spread over the prologues of the statistics kernel's workgroups, one knot per
+  // wave, when there are enough of them; else a few extra workgroups at the front of its grid.
+  // Without a statistics kernel (log-sum-exp supplied) the accumulation kernel carries it the
+  // same way.  Second phase (budgets): where the caller says - extra workgroups at the front of
+  // the accumulation kernel (b_in_accum; the vertices then need a launch of their own if there
+  // is no statistics kernel), or with the selection.  Extra workgroups are padded to a multiple
+  // of 8 so that a chunk lands on the same XCD (and its L2) in both passes.
+  const int64_t wgsA = (int64_t)tabA.tile0[tabA.n_seqs] * g.n_kv_heads * g.n_layers;
+  const int64_t wgsB = (int64_t)tabB.tile0[tabB.n_seqs] * g.n_kv_heads * g.n_layers;
+  int frontA = 0, bppA = 1, spreadA = 0, frontB = 0, bppB = 0, spreadB = 0;
+  bool vertices_alone = false;
+  if (aio) {
+    io = *aio;
+    const int64_t n_knots = (int64_t)aio->n_problems * aio->n_heads * aio->n_grid;
+    const int bpp = alloc_blocks_a(aio->n_heads, aio->n_grid);
+    if (!lse) {
+      spreadA = alloc_spread_knots(n_knots, wgsA);
+      if (!spreadA) { bppA = bpp; frontA = (aio->n_problems * bpp + 7) / 8 * 8; }
+      if (b_in_accum) frontB = (aio->n_problems + 7) / 8 * 8;
+    } else if (b_in_accum) {
+      vertices_alone = true;
+      frontB = (aio->n_problems + 7) / 8 * 8;
+    } else {
+      spreadB = alloc_spread_knots(n_knots, wgsB);
+      if (!spreadB) { bppB = bpp; frontB = (aio->n_problems * bpp + 7) / 8 * 8; }
+    }
+  }
+  dim3 gridA(tabA.tile0[tabA.n_seqs] + frontA, g.n_kv_heads, g.n_layers);
+  dim3 gridB(tabB.tile0[tabB.n_seqs] + frontB, g.n_kv_heads, g.n_layers);
   if (!lse)
-    launch_staged(kStStats, score_stats_kernel<F32, D, NBM, RG>, gridA, dim3(256), st, g, tabA,
-                  (const char*)q, (const char*)k, partial, lay.max_chunks, lay.rows_padded);
+    launch_staged(kStStats, score_stats_kernel<F32, D, NBM, RG>, gridA, dim3(256), st, g, tabA, io, frontA, bppA,
+                  spreadA, (const char*)q, (const char*)k, lpart, lay.rows_padded);
+  else if (vertices_alone)
+    launch_allocate_vertices(*aio, st);
   launch_staged(kStAccum, score_accum_kernel<F32, D, NBM, RG>, gridB, dim3(256), st, g, tabB, io,
-                n_alloc, bpp, (const char*)q, (const char*)k, (const float2*)partial, lse, raw,
+                frontB, bppB, spreadB, (const char*)q, (const char*)k, (const float*)lpart, lse, raw,
                 range, lay.max_chunks, lay.rows_padded);
   return check_launch();
 }
 
 template <bool F32, int D, int NBM>
 static int launch_raw_rg(const HostCfg& hc, const WsLayout& lay, const void* q, const void* k,
-                         const float* lse, const AllocIO* aio, char* ws, hipStream_t st) {
+                         const float* lse, const AllocIO* aio, bool b_in_accum, char* ws, hipStream_t st) {
   switch (hc.g.row_groups) {
-    case 1: return launch_raw_t<F32, D, NBM, 1>(hc, lay, q, k, lse, aio, ws, st);
-    case 2: return launch_raw_t<F32, D, NBM, 2>(hc, lay, q, k, lse, aio, ws, st);
-    case 4: return launch_raw_t<F32, D, NBM, 4>(hc, lay, q, k, lse, aio, ws, st);
+    case 1: return launch_raw_t<F32, D, NBM, 1>(hc, lay, q, k, lse, aio, b_in_accum, ws, st);
+    case 2: return launch_raw_t<F32, D, NBM, 2>(hc, lay, q, k, lse, aio, b_in_accum, ws, st);
+    case 4: return launch_raw_t<F32, D, NBM, 4>(hc, lay, q, k, lse, aio, b_in_accum, ws, st);
   }
   return LUKV_EINVAL;
 }
 
 int launch_score_raw(const HostCfg& hc, const WsLayout& lay, const void* q, const void* k,
-                     const float* lse, const AllocIO* aio, char* ws, hipStream_t st) {
+                     const float* lse, const AllocIO* aio, bool b_in_accum, char* ws, hipStream_t st) {
   const Geom& g = hc.g;
-  if (!g.f32 && g.head_dim == 128) return launch_raw_rg<false, 128, 4>(hc, lay, q, k, lse, aio, ws, st);
-  if (!g.f32 && g.head_dim == 64) return launch_raw_rg<false, 64, 4>(hc, lay, q, k, lse, aio, ws, st);
-  if (g.f32 && g.head_dim == 64) return launch_raw_rg<true, 64, 4>(hc, lay, q, k, lse, aio, ws, st);
-  if (g.f32 && g.head_dim == 128) return launch_raw_rg<true, 128, 2>(hc, lay, q, k, lse, aio, ws, st);
+  if (!g.f32 && g.head_dim == 128) return launch_raw_rg<false, 128, 4>(hc, lay, q, k, lse, aio, b_in_accum, ws, st);
+  if (!g.f32 && g.head_dim == 64) return launch_raw_rg<false, 64, 4>(hc, lay, q, k, lse, aio, b_in_accum, ws, st);
+  if (g.f32 && g.head_dim == 64) return launch_raw_rg<true, 64, 4>(hc, lay, q, k, lse, aio, b_in_accum, ws, st);
+  if (g.f32 && g.head_dim == 128) return launch_raw_rg<true, 128, 2>(hc, lay, q, k, lse, aio, b_in_accum, ws, st);
   return LUKV_EDTYPE;
 }
 

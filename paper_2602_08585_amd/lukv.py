@@ -39,7 +39,7 @@ EXPORTS = ("lukv_workspace_bytes", "lukv_allocate_workspace_bytes", "lukv_score"
 # include/lukv_bench.h: instrumentation for programs that time the path
 BENCH_EXPORTS = ("lukv_set_stage_events", "lukv_stage_name", "lukv_bench_stream_read", "lukv_bench_copy")
 LUKV_STATIC_SCRATCH_BYTES = 16 << 20
-LUKV_NUM_STAGES = 7
+LUKV_NUM_STAGES = 9
 LUKV_NUM_STAGE_EVENTS = 2 * LUKV_NUM_STAGES
 
 

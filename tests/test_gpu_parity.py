@@ -58,6 +58,11 @@ def small(name):
                                  dtype=synth.F32),
         # a one-token observation window (rows = G, padded to one 32-row block)
         "bf16_w1": dict(n_q_heads=4, n_kv_heads=1, head_dim=128, seq_lens=[300], window=1, n_sink=2),
+        # 64 heads in the call: the selection takes its whole-head form (one workgroup per head),
+        # the allocation's budget phase rides in the second score kernel
+        "bf16_64heads": dict(n_q_heads=16, n_kv_heads=8, head_dim=64, seq_lens=[1500], window=16, n_layers=8),
+        "bf16_64heads_ragged": dict(n_q_heads=8, n_kv_heads=8, head_dim=128, seq_lens=[700, 1029], window=32,
+                                    n_layers=4, pool_kernel=5),
         # shortest legal context: one prefix token beyond window + sink
         "bf16_short": dict(n_q_heads=4, n_kv_heads=1, head_dim=128, seq_lens=[37], window=32, n_sink=4,
                            keep_ratio=1.0, n_grid=4),
@@ -71,7 +76,7 @@ def small(name):
 
 SMALL = ["bf16_g4_w32", "bf16_g5_w32", "bf16_g4_w64", "bf16_g7_w16_d64", "bf16_ragged", "f32_d128",
          "f32_d64_peaky", "bf16_short", "bf16_g8_w64_rows512", "bf16_mha_pool1_nosink", "bf16_pool31",
-         "f32_d128_rows256", "bf16_w1"]
+         "f32_d128_rows256", "bf16_w1", "bf16_64heads", "bf16_64heads_ragged"]
 
 
 def _problem(name):
@@ -159,7 +164,8 @@ def test_evict_fused_parity(name):
         assert n_band == 0
 
 
-@pytest.mark.parametrize("name", ["tiny", "bf16_g4_w32", "bf16_g5_w32", "bf16_ragged", "f32_d64_peaky"])
+@pytest.mark.parametrize("name", ["tiny", "bf16_g4_w32", "bf16_g5_w32", "bf16_ragged", "f32_d64_peaky", "bf16_64heads",
+                                  "bf16_64heads_ragged"])
 def test_lse_variant_parity(name):
     """Scores and the fused path with the window rows' log-sum-exp supplied (no statistics pass)."""
     print("case", name, flush=True)
@@ -330,20 +336,23 @@ def _guarded(rows, d, dtype, guard=64):
     return idx[guard:guard + rows], ko[guard:guard + rows], vo[guard:guard + rows], untouched
 
 
-def test_rows_outside_the_output_are_never_written():
+@pytest.mark.parametrize("name", ["bf16_g4_w32", "bf16_64heads"])
+def test_rows_outside_the_output_are_never_written(name):
     """Negative or too large row offsets (caller-supplied, or from an infeasible allocation whose
-    b_min is itself negative) are flagged and write nothing outside [0, out_rows)."""
-    print("case rows outside the output", flush=True)
-    wl = small("bf16_g4_w32")
+    b_min is itself negative) are flagged and write nothing outside [0, out_rows).  Both forms of
+    the selection (4 heads: per slice; 64 heads: whole head)."""
+    print("case rows outside the output", name, flush=True)
+    wl = small(name)
     p = Problem(wl)
     L, NL, H, d = wl.seq_lens[0], wl.n_layers, wl.n_kv_heads, wl.head_dim
     rng = np.random.default_rng(78)
     pooled = rng.random((NL, H, L)).astype(np.float32)
     pooled[:, :, -wl.window:] = np.inf
-    budgets = np.array([40, 50, 60, 70], np.int32)
+    n_hi = NL * H
+    budgets = np.array([40, 50, 60] + [70] * (n_hi - 3), np.int32)
     rows = 120
-    # head 0 starts before the buffer, head 1 is in range, head 2 runs over the end, head 3 starts beyond it
-    offsets = np.array([-5, 10, rows - 20, rows + 7, rows + 77], np.int64)
+    # head 0 starts before the buffer, head 1 is in range, head 2 runs over the end, the others start beyond it
+    offsets = np.array([-5, 10, rows - 20] + [rows + 7 + 70 * i for i in range(n_hi - 2)], np.int64)
     idx, ko, vo, untouched = _guarded(rows, d, p.k.dtype)
     status = torch.full((1,), -7, dtype=torch.int32, device="cuda")
     lukv.lukv_select_compact(p.cfg, dev(pooled), dev(budgets), dev(offsets), p.k, p.v, rows, idx, ko, vo, status, p.ws)
@@ -355,7 +364,8 @@ def test_rows_outside_the_output_are_never_written():
     want1 = O.select(pooled[0, 1], 50)
     assert np.array_equal(got[10:60], want1)
     assert np.array_equal(host_bits(ko)[10:60], p.data["k"][0, 1][want1])
-    assert np.array_equal(got[rows - 20:], O.select(pooled[1, 0], 60)[:20])
+    l2, c2 = divmod(2, H)
+    assert np.array_equal(got[rows - 20:], O.select(pooled[l2, c2], 60)[:20])
     # fused path: one head's b_min is negative, so the allocation is infeasible and hands the
     # b_min back as budgets; the selection clamps them and its offsets stay inside the output
     alloc = {k: v.copy() for k, v in p.alloc.items()}
@@ -412,21 +422,25 @@ def _adversarial_scores(kind, rng, shape):
     return x.reshape(shape)
 
 
+@pytest.mark.parametrize("n_layers", [1, 8])
 @pytest.mark.parametrize("kind", ["all_equal", "two_values", "quantised", "narrow_band", "wide_signed",
                                   "denormal_and_zero", "mostly_zero_few_heavy", "lognormal"])
-def test_select_adversarial_score_distributions(kind):
-    print("case", kind, flush=True)
-    wl = synth.Workload(name="sel_" + kind, n_layers=1, n_q_heads=4, n_kv_heads=4, head_dim=64,
+def test_select_adversarial_score_distributions(kind, n_layers):
+    """n_layers = 1: 8 heads, the per-slice form of the selection; 8: 64 heads, the whole-head form."""
+    print("case", kind, n_layers, flush=True)
+    wl = synth.Workload(name="sel_" + kind, n_layers=n_layers, n_q_heads=4, n_kv_heads=4, head_dim=64,
                         seq_lens=[20011, 5000], window=16, pool_kernel=7, n_sink=4, dtype=synth.BF16,
                         keep_ratio=0.2, n_grid=8, heavy_frac=0.0, seed=99, q_gain=64.0)
-    p = Problem(wl)
-    rng = np.random.default_rng(zlib.crc32(kind.encode()))
-    pooled = _adversarial_scores(kind, rng, (1, wl.n_kv_heads, wl.total_len))
+    p = Problem(wl, workers=4)
+    rng = np.random.default_rng(zlib.crc32(kind.encode()) + n_layers)
+    pooled = _adversarial_scores(kind, rng, (n_layers, wl.n_kv_heads, wl.total_len))
     cu = wl.cu_seqlens
     budgets = []
     for s in range(wl.n_seqs):
         L = int(cu[s + 1] - cu[s])
-        budgets += [L // 3, 1, L - 1, int(rng.integers(1, L))]
+        for l in range(n_layers):
+            budgets += [L // 3, 1, L - 1, int(rng.integers(1, L))] if l % 2 == 0 else \
+                [int(rng.integers(0, L + 1)) for _ in range(4)]
     budgets = np.array(budgets, np.int32)
     offsets = O.offsets_of(budgets)
     out = p.new_outputs(rows=int(offsets[-1]))
@@ -437,13 +451,14 @@ def test_select_adversarial_score_distributions(kind):
     assert int(out["status"][0]) == 0
     kept, ko, vo = out["kept_idx"].cpu().numpy(), host_bits(out["k_out"]), host_bits(out["v_out"])
     for s in range(wl.n_seqs):
-        for c in range(wl.n_kv_heads):
-            hi = s * wl.n_kv_heads + c
-            a, b = int(offsets[hi]), int(offsets[hi + 1])
-            want = O.select(pooled[0, c, cu[s]:cu[s + 1]], int(budgets[hi]))
-            assert np.array_equal(kept[a:b], want), (kind, s, c)
-            assert np.array_equal(ko[a:b], p.data["k"][0, c, cu[s]:cu[s + 1]][want])
-            assert np.array_equal(vo[a:b], p.data["v"][0, c, cu[s]:cu[s + 1]][want])
+        for l in range(n_layers):
+            for c in range(wl.n_kv_heads):
+                hi = (s * n_layers + l) * wl.n_kv_heads + c
+                a, b = int(offsets[hi]), int(offsets[hi + 1])
+                want = O.select(pooled[l, c, cu[s]:cu[s + 1]], int(budgets[hi]))
+                assert np.array_equal(kept[a:b], want), (kind, s, l, c)
+                assert np.array_equal(ko[a:b], p.data["k"][l, c, cu[s]:cu[s + 1]][want])
+                assert np.array_equal(vo[a:b], p.data["v"][l, c, cu[s]:cu[s + 1]][want])
 
 
 def test_host_side_refusals_enqueue_nothing():
@@ -678,6 +693,26 @@ def test_evict_long_context_32_layers():
             n_band += check_band(kept_h[lo:hi_end], O.select(S[c], int(b_ref[hi])), S[c], BAND)
     print("long_128k (32 layers) band-only index differences in layers 0/15/31:", n_band)
     assert n_band <= 3 * MAX_BAND_SWAPS_PER_LAYER
+
+
+def test_scores_do_not_depend_on_the_call_shape():
+    """A layer scored alone and the same layer inside an 8-layer call (whose workgroups stream
+    chunks of 1024 or 2048 keys instead of 512) give bitwise the same scores: the softmax
+    statistics are merged per granule of keys fixed by the sequence length, not by the chunking."""
+    print("case call shape", flush=True)
+    wl8 = dataclasses.replace(synth.workload("8b_full_20"), n_layers=8, name="8b_full_20_8layers")
+    p8 = Problem(wl8, workers=8)
+    pooled8 = torch.full((8, wl8.n_kv_heads, wl8.total_len), float("nan"), device="cuda")
+    lukv.lukv_score(p8.cfg, p8.q, p8.k, pooled8, p8.ws)
+    torch.cuda.synchronize()
+    for l in (0, 5):
+        wl1 = dataclasses.replace(wl8, n_layers=1)
+        data1 = {key: p8.data[key][l:l + 1].copy() for key in ("q_win", "k", "v")}
+        p1 = Problem(wl1, data=data1)
+        pooled1 = torch.full((1, wl1.n_kv_heads, wl1.total_len), float("nan"), device="cuda")
+        lukv.lukv_score(p1.cfg, p1.q, p1.k, pooled1, p1.ws)
+        torch.cuda.synchronize()
+        assert torch.equal(pooled1[0].view(torch.int32), pooled8[l].view(torch.int32)), l
 
 
 def _calibration_curves(wl, n_queries):
