@@ -1,14 +1,24 @@
 #!/usr/bin/env python3
 """Benchmark of the fused LU-KV eviction step (score + allocate + top-k + compact) on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 8b_32k|long_128k] [--layers N]
 
 A step is one lukv_evict call over one 8B-shaped layer at 32k context (32 q / 8 kv heads,
 d=128, w=32, pool 7, bf16, 20 % budget, 64-point curves), inputs resident in HBM.  Steps
 rotate over 16 distinct seeded input sets (2 GiB of K/V) so that K and V stream from HBM
 rather than from the last-level cache.  Prints ONE JSON line: whole-step throughput in
-context tokens/s, the roofline of the dominant kernel (HIP events recorded by the library
-between its stages, on the launch stream), and the CPU oracle timed on this host.
+context tokens/s (eager launches; the figure the line's `value` carries), per-step median and
+minimum from events around single steps, the roofline of the dominant kernel (HIP events the
+library records around each stage's kernel, on the launch stream) against the nominal HBM peak
+and against the streaming-read and copy rates measured in this same run, the CPU oracle timed on
+this host (all cores and one thread), and three separately named extra figures: the step with
+the log-sum-exp supplied, the step replayed from a captured HIP graph, and one decode step's
+attention over the compacted cache.
+
+--config long_128k times one layer of the long-context configuration (131072 tokens, w = 64,
+5 % budget) instead: there the score kernels are bound by the exponential rate, and the line's
+roofline says so.  --layers N times N layers of the full-prefill configuration in one call.
+Neither is the headline workload.
 """
 from __future__ import annotations
 
@@ -25,16 +35,35 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 N_SETS = 16
-N_CPU_SETS = 8      # input sets the CPU oracle is timed on (about 10 s of host work)
+N_CPU_SETS = 8            # input sets kept on the host for the CPU oracle
+CPU_SECONDS = 10.0        # host time given to each CPU leg (all cores, one thread)
 HBM_PEAK_GBS = 8000.0
+# v_exp_f32 issues at a quarter of the vector rate: 4 lanes per clock per SIMD,
+# 256 CUs x 4 SIMDs x 4 x 2.4 GHz
+EXP_PEAK_GEXPS = 256 * 4 * 4 * 2.4
+CEILING_BYTES = 64 << 20  # size of the plain read / copy passes that measure what the GPU sustains
 
 
 def _hip():
     """The HIP runtime this process already uses (torch's), for event create/elapsed."""
     for line in open("/proc/self/maps"):
         if "libamdhip64" in line:
-            return ctypes.CDLL(line.split()[-1])
+            lib = ctypes.CDLL(line.split()[-1])
+            lib.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+            lib.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+            lib.hipEventDestroy.argtypes = [ctypes.c_void_p]
+            return lib
     raise RuntimeError("HIP runtime not loaded")
+
+
+def _cpu_model() -> str:
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
 
 
 def main() -> int:
@@ -43,20 +72,19 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=320)
     ap.add_argument("--warmup", type=int, default=32)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--config", choices=("8b_32k", "long_128k"), default="8b_32k",
+                    help="8b_32k (default): the headline workload.  long_128k: one layer of the "
+                         "long-context configuration, reported against the exponential rate")
     ap.add_argument("--layers", type=int, default=1,
-                    help="1 (default): the headline workload, one 8B-shaped layer at 32k.  N > 1: "
-                         "N layers of the full-prefill configuration in ONE call (one global "
+                    help="N > 1: N layers of the full-prefill configuration in ONE call (one global "
                          "allocation over 8N layer-heads); an extra figure, no CPU baseline")
-    ap.add_argument("--calibration-copy", action="store_true",
-                    help="also run a plain elementwise pass over 256 MiB (read 256 MiB, write 256 MiB) "
-                         "four times before the warm-up: the known-size kernel that scales the "
-                         "rocprofv3 FETCH_SIZE / WRITE_SIZE counters (profiles/)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.stderr.write("bench.py: this build runs on ONE GPU only (the path shards over heads and "
                          "layers without communication); --gpus %d is not supported\n" % args.gpus)
         return 2
 
+    import dataclasses
     import numpy as np
     import torch
     from paper_2602_08585_amd import lukv, synth
@@ -64,24 +92,32 @@ def main() -> int:
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     lukv.load_library()
+    hip = _hip()
     NL = args.layers
-    if NL == 1:
+    headline = NL == 1 and args.config == "8b_32k"
+    if args.config == "long_128k":
+        wl = dataclasses.replace(synth.workload("long_128k"), n_layers=1, name="long_128k_1layer")
+        NL = 1
+        n_sets = 4                      # 512 MiB of K/V each
+    elif NL == 1:
         wl = synth.workload("8b_32k")
+        n_sets = N_SETS
     else:
-        import dataclasses
         wl = dataclasses.replace(synth.workload("8b_full_20"), n_layers=NL, name="8b_full_20_%dlayers" % NL)
+        n_sets = max(1, N_SETS // NL)
+    if not headline:
         args.no_cpu_baseline = True
-    n_sets = max(1, N_SETS // NL)
     L, d, Hkv, Hq, w = wl.seq_lens[0], wl.head_dim, wl.n_kv_heads, wl.n_q_heads, wl.window
+    G = Hq // Hkv
 
-    # ---- inputs: N_SETS distinct layers' worth of Q/K/V, one allocation problem ------------
+    # ---- inputs: distinct layers' worth of Q/K/V, one allocation problem ---------------------
     def up(x):
         t = torch.from_numpy(np.ascontiguousarray(x))
         return (t.view(torch.bfloat16) if x.dtype == np.uint16 else t).cuda()
 
     sets, host_sets = [], []
     for i in range(n_sets):
-        data = synth.make_qkv(wl, layers=list(range(i * NL, (i + 1) * NL)))
+        data = synth.make_qkv(wl, layers=list(range(i * NL, (i + 1) * NL)), workers=8)
         if i < N_CPU_SETS and not args.no_cpu_baseline:
             host_sets.append(data)
         sets.append((up(data["q_win"]), up(data["k"]), up(data["v"])))
@@ -100,24 +136,26 @@ def main() -> int:
     v_out = torch.zeros((rows, d), dtype=torch.bfloat16, device="cuda")
     status = torch.zeros(wl.n_seqs + 1, dtype=torch.int32, device="cuda")
 
-    def step(i):
+    def step(i, stream=None, ko=None, vo=None):
         q, k, v = sets[i % n_sets]
         lukv.lukv_evict(cfg, q, k, v, wl.n_grid, curves, knots, b_min, b_max, B, budgets, offsets,
-                        kept, k_out, v_out, None, status, ws)
+                        kept, k_out if ko is None else ko, v_out if vo is None else vo, None, status, ws,
+                        stream=stream)
 
     # the window rows' log-sum-exp of every input set: an INPUT of the lse variant (what a prefill
     # attention kernel leaves behind), prepared with torch outside every timed region
     def window_lse(q, k):
-        G = Hq // Hkv
         j = torch.arange(L, device="cuda")[None, None, :]
         i = torch.arange(w, device="cuda")[None, :, None]
-        rows = []
+        out = []
         for l in range(NL):
-            kk = k[l].float().repeat_interleave(G, dim=0)                  # [Hq, L, d]
-            logits = torch.einsum("hid,hjd->hij", q[l].float(), kk) / (d ** 0.5)
-            logits = logits.masked_fill(j > L - w + i, float("-inf"))
-            rows.append(torch.logsumexp(logits, dim=2))
-        return torch.stack(rows).contiguous()                              # [NL, Hq, w]
+            per_head = []
+            for c in range(Hkv):       # one kv head at a time: the logits of a long context are large
+                logits = torch.einsum("hid,jd->hij", q[l, c * G:(c + 1) * G].float(), k[l, c].float()) / (d ** 0.5)
+                logits = logits.masked_fill(j > L - w + i, float("-inf"))
+                per_head.append(torch.logsumexp(logits, dim=2))
+            out.append(torch.cat(per_head))
+        return torch.stack(out).contiguous()                              # [NL, Hq, w]
     lses = [window_lse(q, k) for q, k, _ in sets]
 
     def step_lse(i):
@@ -125,50 +163,66 @@ def main() -> int:
         lukv.lukv_evict_lse(cfg, q, k, v, lses[i % n_sets], wl.n_grid, curves, knots, b_min, b_max, B,
                             budgets, offsets, kept, k_out, v_out, None, status, ws)
 
-    if args.calibration_copy:
-        src = torch.zeros(64 * 1024 * 1024, dtype=torch.float32, device="cuda")
-        dst = torch.empty_like(src)
-        for _ in range(4):
-            torch.add(src, 1.0, out=dst)
+    def wall(fn, n_warm, n):
+        for i in range(n_warm):
+            fn(i)
         torch.cuda.synchronize()
-        del src, dst
+        t0 = time.perf_counter()
+        for i in range(n):
+            fn(i)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / n
 
     # ---- timed region: W warm-up steps, then exactly K steps --------------------------------
     # (the interpreter's cyclic collector stays off while the host enqueues: a full collection
     # of torch's heap takes tens of milliseconds, hundreds of steps' worth)
     gc.collect()
     gc.disable()
-    for i in range(args.warmup):
-        step(i)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(i)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    ms_per_step = dt * 1e3 / args.steps
+    ms_per_step = wall(step, args.warmup, args.steps)
     assert int(status.abs().sum()) == 0
 
     # the same K steps with the log-sum-exp supplied (no statistics pass over K): a second,
     # separately named figure, never the headline value
-    for i in range(args.warmup):
-        step_lse(i)
+    ms_per_step_lse = wall(step_lse, args.warmup, args.steps)
+    assert int(status.abs().sum()) == 0
+
+    # ---- single steps between events: median and minimum --------------------------------------
+    n_single = min(args.steps, 200)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(n_single + 1)]
+    marks[0].record()
+    for i in range(n_single):
+        step(i)
+        marks[i + 1].record()
+    torch.cuda.synchronize()
+    single_us = np.array([marks[i].elapsed_time(marks[i + 1]) * 1e3 for i in range(n_single)])
+
+    # ---- the step replayed from a captured HIP graph (one graph holds one step per input set) ---
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step(0, stream=side)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        for i in range(n_sets):
+            step(i, stream=side)
+    n_replays = max(1, args.steps // n_sets)
+    for _ in range(2):
+        graph.replay()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(args.steps):
-        step_lse(i)
+    for _ in range(n_replays):
+        graph.replay()
     torch.cuda.synchronize()
-    ms_per_step_lse = (time.perf_counter() - t0) * 1e3 / args.steps
+    ms_per_step_graph = (time.perf_counter() - t0) * 1e3 / (n_replays * n_sets)
     assert int(status.abs().sum()) == 0
+    del graph
     gc.enable()
 
     # ---- per-kernel durations: the library attaches the caller's start / stop events to the
     # dispatch of every stage's kernel (on the launch stream), so an elapsed time is the kernel's
     # own duration, as a profiler reports it ------------------------------------------------------
-    hip = _hip()
-    hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
-    hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
-    hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
     n_ev = lukv.LUKV_NUM_STAGE_EVENTS
     names = [lukv.lukv_stage_name(j) for j in range(lukv.LUKV_NUM_STAGES)]
     used = [j for j, n in enumerate(names) if n not in ("allocate", "pool")]
@@ -187,89 +241,202 @@ def main() -> int:
         step(i)
     lukv.lukv_set_stage_events(None)
     torch.cuda.synchronize()
-    stage_ms = np.zeros(len(used))
-    stage_n = np.zeros(len(used))
+    per_stage = {}
     for arr in ev_sets:
-        for i, st_i in enumerate(used):
+        for st_i in used:
             ms = ctypes.c_float()
             # a stage this call shape does not launch leaves its events unrecorded
             if hip.hipEventElapsedTime(ctypes.byref(ms), arr[2 * st_i], arr[2 * st_i + 1]) == 0:
-                stage_ms[i] += ms.value
-                stage_n[i] += 1
+                per_stage.setdefault(names[st_i], []).append(ms.value * 1e3)
             hip.hipEventDestroy(arr[2 * st_i])
             hip.hipEventDestroy(arr[2 * st_i + 1])
     hip.hipGetLastError()        # the queries of unrecorded events leave an error code behind
-    stages = {names[st_i]: round(float(stage_ms[i] / stage_n[i]) * 1e3, 2) for i, st_i in enumerate(used)
-              if stage_n[i] > 0}
+    stages = {n: round(float(np.mean(v)), 2) for n, v in per_stage.items()}
 
-    # algorithmic bytes per launch of the two streaming score kernels (8B/32k layer)
+    # ---- what this GPU sustains for plain streaming: a read pass and a copy pass over 64 MiB of
+    # cold data (the K of successive input sets), outside the timed region ----------------------
+    sink = torch.zeros(4 * 65536, dtype=torch.int32, device="cuda")
+    dst = torch.empty(CEILING_BYTES, dtype=torch.uint8, device="cuda")
+    kflat = []                  # successive 64 MiB pieces of the input sets' K
+    for s in sets:
+        flat = s[1].reshape(-1).view(torch.uint8)
+        for o in range(0, flat.numel() - CEILING_BYTES + 1, CEILING_BYTES):
+            if len(kflat) < 16:
+                kflat.append(flat[o:o + CEILING_BYTES])
+    assert kflat
+
+    def ceiling(fn):
+        best = []
+        for blocks in (1024, 2048, 4096, 8192):
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(2 * 12)]
+            for i in range(12):
+                ev[2 * i].record()
+                fn(kflat[i % len(kflat)], blocks)
+                ev[2 * i + 1].record()
+            torch.cuda.synchronize()
+            us = [ev[2 * i].elapsed_time(ev[2 * i + 1]) * 1e3 for i in range(2, 12)]
+            best.append(float(np.median(us)))
+        return min(best)
+    read_us = ceiling(lambda src, blocks: lukv.lukv_bench_stream_read(src, CEILING_BYTES, sink, blocks))
+    copy_us = ceiling(lambda src, blocks: lukv.lukv_bench_copy(src, dst, CEILING_BYTES, blocks))
+    read_gbs = CEILING_BYTES / (read_us * 1e-6) / 1e9
+    copy_gbs = 2 * CEILING_BYTES / (copy_us * 1e-6) / 1e9
+    del sink, dst
+
+    # ---- algorithmic bytes ---------------------------------------------------------------------
     esz = 2
     k_bytes = NL * Hkv * L * d * esz
     q_bytes = NL * Hq * w * d * esz
+    sc_bytes = NL * Hkv * L * 4
+    row_bytes = rows * d * esz
     alg = {"score_stats": k_bytes + q_bytes,
-           "score_accum": k_bytes + q_bytes + NL * Hkv * L * 4}
-    dom = max(alg, key=lambda n: stages[n])
-    achieved = alg[dom] / (stages[dom] * 1e-6) / 1e9
+           "score_accum": k_bytes + q_bytes + sc_bytes,
+           "sel_hist": 2 * sc_bytes, "sel_tail": sc_bytes // 8, "sel_head": sc_bytes,
+           "sel_emit": sc_bytes + rows * 4 + 4 * row_bytes,
+           "sel_gather": rows * 4 + 4 * row_bytes}
     # whole-step algorithmic traffic (streaming model): K twice, Q, scores w+r, idx w+r,
     # gather reads of kept K and V rows, compacted K and V writes
-    b_alg = 2 * k_bytes + q_bytes + 2 * NL * Hkv * L * 4 + 2 * rows * 4 + 2 * rows * d * esz + 2 * rows * d * esz
-    # measured HBM bytes per launch of that kernel: rocprofv3 counter runs of this same command,
-    # scaled by the calibration copy, stored beside their summaries (None if not measured)
-    traffic, traffic_detail = None, None
-    tpath = os.path.join(ROOT, "profiles", "lukv_evict_8b_32k_hbm_traffic.json")
-    if NL == 1 and os.path.exists(tpath):
-        rec = json.load(open(tpath)).get(dom)
-        if rec:
-            traffic = rec["fetch_bytes"] + rec["write_bytes"]
-            traffic_detail = rec
-    roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
-                "traffic_detail": traffic_detail,
-                "alg_bytes_per_launch": alg[dom], "kernel_us": stages[dom],
-                "step_alg_bytes": b_alg,
-                "step_frac_of_hbm": round(b_alg / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-                "stage_us": stages}
+    b_alg = 2 * k_bytes + q_bytes + 2 * sc_bytes + 2 * rows * 4 + 4 * row_bytes
+    score_kernels = [n for n in ("score_stats", "score_accum") if n in stages]
+    dom = max(score_kernels, key=lambda n: stages[n])
+    kernel_frac = {n: {"alg_bytes": alg[n], "us": stages[n],
+                       "GBs": round(alg[n] / (stages[n] * 1e-6) / 1e9, 1),
+                       "frac_of_hbm_peak": round(alg[n] / (stages[n] * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
+                       "frac_of_read_ceiling": round(alg[n] / (stages[n] * 1e-6) / 1e9 / read_gbs, 4)}
+                   for n in stages if n in alg}
+    step_gbs = b_alg / (ms_per_step * 1e-3) / 1e9
+    ceil = {"stream_read_GBs": round(read_gbs, 1), "copy_GBs": round(copy_gbs, 1), "bytes": CEILING_BYTES,
+            "how": "plain 16-byte grid-stride kernels of liblukv over 64 MiB of cold data, median of 10 "
+                   "launches between events, best of 1024/2048/4096/8192 workgroups; measured in this run"}
+    if args.config == "long_128k":
+        # exponentials per launch: every (window row, key) pair of every head once
+        n_exp = NL * Hkv * G * w * (L - w)
+        achieved = n_exp / (stages[dom] * 1e-6) / 1e9
+        roofline = {"bound": "exp", "kernel": dom, "achieved": round(achieved, 1), "peak": EXP_PEAK_GEXPS,
+                    "unit": "Gexp/s", "frac": round(achieved / EXP_PEAK_GEXPS, 4), "traffic": None,
+                    "peak_derivation": "v_exp_f32 at a quarter of the vector rate: 256 CUs x 4 SIMDs x 4 "
+                                       "lanes/clock x 2.4 GHz",
+                    "exp_per_launch": n_exp, "kernel_us": stages[dom],
+                    "hbm_view": kernel_frac[dom], "ceiling": ceil, "stage_us": stages, "kernels": kernel_frac}
+    else:
+        achieved = alg[dom] / (stages[dom] * 1e-6) / 1e9
+        # measured HBM bytes per launch of that kernel: rocprofv3 counter runs of this same command,
+        # scaled by the copy pass of known size above, stored beside their summaries
+        traffic, traffic_detail = None, None
+        tpath = os.path.join(ROOT, "profiles", "lukv_evict_8b_32k_hbm_traffic.json")
+        if headline and os.path.exists(tpath):
+            rec = json.load(open(tpath)).get(dom)
+            if rec:
+                traffic = rec["fetch_bytes"] + rec["write_bytes"]
+                traffic_detail = dict(rec, source="rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this command, "
+                                                  "stored under profiles/ (counters cannot be read from "
+                                                  "inside the run)")
+        roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+                    "traffic_detail": traffic_detail,
+                    "frac_of_read_ceiling": round(achieved / read_gbs, 4),
+                    "alg_bytes_per_launch": alg[dom], "kernel_us": stages[dom],
+                    "ceiling": ceil,
+                    "step_alg_bytes": b_alg,
+                    "step_frac_of_hbm": round(step_gbs / HBM_PEAK_GBS, 4),
+                    "step_frac_of_copy_ceiling": round(step_gbs / copy_gbs, 4),
+                    "stage_us": stages, "kernels": kernel_frac}
+
+    # ---- one decode step's attention over the compacted cache (Eq. 3's consumer) ---------------
+    decode = None
+    if headline:
+        n_dec = 12                                   # 12 packed caches of 26.8 MB: more than the last-level cache
+        caches = []
+        for i in range(n_dec):
+            ko, vo = torch.empty_like(k_out), torch.empty_like(v_out)
+            step(i, ko=ko, vo=vo)
+            caches.append((ko, vo))
+        qd = up(synth.make_decode_queries(wl, layers=[0]))
+        res = torch.zeros((NL, Hq, wl.n_seqs, d), dtype=torch.float32, device="cuda")
+        dws = lukv.alloc_workspace(lukv.lukv_decode_workspace_bytes(cfg))
+        for i in range(n_dec):
+            lukv.lukv_decode_attention(cfg, qd, caches[i][0], caches[i][1], offsets, res, dws)
+        n_rep = 48
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(n_rep + 1)]
+        ev[0].record()
+        for i in range(n_rep):
+            lukv.lukv_decode_attention(cfg, qd, caches[i % n_dec][0], caches[i % n_dec][1], offsets, res, dws)
+            ev[i + 1].record()
+        torch.cuda.synchronize()
+        dus = np.array([ev[i].elapsed_time(ev[i + 1]) * 1e3 for i in range(n_rep)])
+        dec_bytes = 2 * row_bytes + Hq * d * esz + Hq * d * 4
+        decode = {"what": "lukv_decode_attention: one decode query per head over the packed cache the step "
+                          "leaves (K and V rows of all 8 heads, %d rows), 12 rotating caches" % rows,
+                  "us_median": round(float(np.median(dus)), 2), "us_min": round(float(dus.min()), 2),
+                  "alg_bytes": dec_bytes,
+                  "GBs": round(dec_bytes / (float(np.median(dus)) * 1e-6) / 1e9, 1),
+                  "frac_of_hbm_peak": round(dec_bytes / (float(np.median(dus)) * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
+                  "frac_of_read_ceiling": round(dec_bytes / (float(np.median(dus)) * 1e-6) / 1e9 / read_gbs, 4)}
+        del caches
 
     # ---- CPU oracle on the same workload (one full layer = one step), this host -------------
     cpu = None
     if not args.no_cpu_baseline:
         from oracle import lukv_oracle as O
-        try:
-            from threadpoolctl import threadpool_info
-            cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
-        except Exception:
-            cores = 1
-        t0 = time.perf_counter()
-        for h in host_sets:
-            ref = O.evict(h["q_win"], h["k"], h["v"], wl.cu_seqlens, Hkv, w, wl.pool_kernel, wl.n_sink,
-                          alloc["curves"], alloc["knots"], alloc["b_min"], alloc["b_max"], alloc["B"])
-        t_cpu = (time.perf_counter() - t0) / len(host_sets)
-        # cheap sanity on the same inputs: budgets bit-exact against what the GPU produced for set 0
+        from threadpoolctl import threadpool_info, threadpool_limits
+
+        def oracle_steps(seconds):
+            n, t0, ref = 0, time.perf_counter(), None
+            while n < 2 or time.perf_counter() - t0 < seconds:
+                h = host_sets[n % len(host_sets)]
+                ref = O.evict(h["q_win"], h["k"], h["v"], wl.cu_seqlens, Hkv, w, wl.pool_kernel, wl.n_sink,
+                              alloc["curves"], alloc["knots"], alloc["b_min"], alloc["b_max"], alloc["B"])
+                n += 1
+            return (time.perf_counter() - t0) / n, n, ref
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        t_all, n_all, ref = oracle_steps(CPU_SECONDS)
+        with threadpool_limits(limits=1):
+            t_one, n_one, _ = oracle_steps(CPU_SECONDS)
+        # cheap sanity on the same inputs: budgets bit-exact against what the GPU produced
         step(0)
         torch.cuda.synchronize()
         parity_ok = bool(np.array_equal(budgets.cpu().numpy(), ref["budgets"]))
-        cpu = {"value": round(L / t_cpu, 1), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
-               "sample": "%d full steps (8b_32k layers) of the numpy fp64 oracle, %.2f s each"
-                         % (len(host_sets), t_cpu),
+        cpu = {"value": round(L / t_all, 1), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+               "sample": "%d full steps (8b_32k layers) of the numpy fp64 oracle, %.2f s each, BLAS on %d threads"
+                         % (n_all, t_all, cores),
+               "single_thread": {"value": round(L / t_one, 1), "unit": "tokens/s", "cores": 1,
+                                 "sample": "%d full steps, %.2f s each, BLAS limited to one thread"
+                                           % (n_one, t_one)},
+               "cpu_model": _cpu_model(), "logical_cpus": os.cpu_count(),
                "budgets_match_gpu": parity_ok}
 
+    if args.config == "long_128k":
+        workload = ("long_128k, one layer: 32 q / 8 kv heads, d=128, L=131072, w=64, pool 7, bf16, B=%d (5%%), "
+                    "64-point curves; %d rotating input sets; NOT the headline workload" % (rows, n_sets))
+    elif NL == 1:
+        workload = ("8b_32k: 1 layer, 32 q / 8 kv heads, d=128, L=32768, w=32, pool 7, bf16, B=52428 (20%), "
+                    "64-point curves; 16 rotating input sets")
+    else:
+        workload = ("%s: %d layers in one call, 32 q / 8 kv heads, d=128, L=32768, w=32, pool 7, bf16, "
+                    "B=%d (20%%) allocated over %d layer-heads; %d input set(s); NOT the headline "
+                    "workload" % (wl.name, NL, rows, NL * Hkv, n_sets))
     out = {"metric": "evicted-context tokens/sec (score+allocate+topk+compact), 32k ctx; % of HBM BW",
            "value": round(L / (ms_per_step * 1e-3), 1), "unit": "tokens/s", "n_gpus": 1,
            "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
            "data": "synthetic",
-           "config": {"workload": ("8b_32k: 1 layer, 32 q / 8 kv heads, d=128, L=32768, w=32, pool 7, "
-                                   "bf16, B=52428 (20%), 64-point curves; 16 rotating input sets") if NL == 1
-                      else ("%s: %d layers in one call, 32 q / 8 kv heads, d=128, L=32768, w=32, pool 7, bf16, "
-                            "B=%d (20%%) allocated over %d layer-heads; %d input set(s); NOT the headline "
-                            "workload" % (wl.name, NL, rows, NL * Hkv, n_sets)),
-                      "n_input_sets": n_sets, "n_layers": NL,
-                      "layer_tokens_per_s": round(NL * L / (ms_per_step * 1e-3), 1)},
+           "config": {"workload": workload, "n_input_sets": n_sets, "n_layers": NL,
+                      "layer_tokens_per_s": round(NL * L / (ms_per_step * 1e-3), 1),
+                      "launch_mode": "eager (the headline value); graph_replay is reported beside it"},
+           "step_us": {"wall_mean": round(ms_per_step * 1e3, 2), "median": round(float(np.median(single_us)), 2),
+                       "min": round(float(single_us.min()), 2), "n": n_single,
+                       "how": "wall_mean: host clock over the K timed steps; median / min: events around "
+                              "each of n single steps"},
            "roofline": roofline, "cpu_baseline": cpu,
            "lse_variant": {"what": "lukv_evict_lse: window rows' log-sum-exp supplied by the caller, "
                                    "statistics pass over K skipped (other workload, not the headline)",
                            "ms_per_step": round(ms_per_step_lse, 5),
-                           "value": round(L / (ms_per_step_lse * 1e-3), 1), "unit": "tokens/s"}}
+                           "value": round(L / (ms_per_step_lse * 1e-3), 1), "unit": "tokens/s"},
+           "graph_replay": {"what": "the same lukv_evict steps captured once into a HIP graph (%d steps, one "
+                                    "per input set) and replayed; not the headline" % n_sets,
+                            "ms_per_step": round(ms_per_step_graph, 5),
+                            "value": round(L / (ms_per_step_graph * 1e-3), 1), "unit": "tokens/s"},
+           "decode_variant": decode}
     print(json.dumps(out))
     return 0
 

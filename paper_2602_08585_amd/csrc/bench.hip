@@ -16,17 +16,23 @@ void stage_events(int stage, hipEvent_t* start, hipEvent_t* stop) {
   if (2 * stage + 1 < g_n_stage_events) *stop = static_cast<hipEvent_t>(g_stage_events[2 * stage + 1]);
 }
 
-// every 16-byte word once, grid-strided, four loads in flight per thread
+// every 16-byte word once, grid-strided, eight loads in flight per thread; one word per wave
+// goes to the sink so that the loads cannot be dropped
 __global__ __launch_bounds__(256) void stream_read_kernel(const u32x4* src, int64_t n16, unsigned* sink) {
   const int64_t stride = (int64_t)gridDim.x * 256;
   int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
   unsigned acc = 0;
-  for (; i + 3 * stride < n16; i += 4 * stride) {
-    const u32x4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
-    acc += a.x ^ b.y ^ c.z ^ d.w;
+  for (; i + 7 * stride < n16; i += 8 * stride) {
+    u32x4 v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = src[i + u * stride];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc += v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
   }
   for (; i < n16; i += stride) acc += src[i].x;
-  sink[blockIdx.x * 256 + threadIdx.x] = acc;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
+  if ((threadIdx.x & 63) == 0) sink[blockIdx.x * 4 + (threadIdx.x >> 6)] = acc;
 }
 
 __global__ __launch_bounds__(256) void copy_kernel(const u32x4* src, u32x4* dst, int64_t n16) {

@@ -211,7 +211,8 @@ __global__ __launch_bounds__(256, (F32 && D == 128) ? 1 : 2) void score_stats_ke
   const int kvh = blockIdx.y, layer = blockIdx.z;
   const int tok0 = tab.cu[seq], L = tab.cu[seq + 1] - tok0, P = L - g.window;
   const int hi = (seq * g.n_layers + layer) * g.n_kv_heads + kvh;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, hf = lane >> 5;
+  // (the wave index is uniform over a wave: saying so keeps what derives from it in scalar registers)
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63, hf = lane >> 5;
   constexpr int n_kt = T::kWaveCols;
   const int kt = wave % n_kt, rg = wave / n_kt;
   const int blk0 = rg * g.blocks_per_group;
@@ -389,7 +390,8 @@ __global__ __launch_bounds__(256, (F32 && D == 128) ? 1 : 2) void score_accum_ke
   const int kvh = blockIdx.y, layer = blockIdx.z;
   const int tok0 = tab.cu[seq], L = tab.cu[seq + 1] - tok0, P = L - g.window;
   const int hi = (seq * g.n_layers + layer) * g.n_kv_heads + kvh;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, hf = lane >> 5;
+  // (the wave index is uniform over a wave: saying so keeps what derives from it in scalar registers)
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63, hf = lane >> 5;
   constexpr int n_kt = T::kWaveCols;
   const int kt = wave % n_kt, rg = wave / n_kt;
   const int blk0 = rg * g.blocks_per_group;
@@ -579,9 +581,13 @@ __global__ __launch_bounds__(256, (F32 && D == 128) ? 1 : 2) void score_accum_ke
         for (int t = 1; t < RG; ++t) col += colred[t * n_kt + kt][lane & 31];
       }
     }
-    if (rg == 0 && lane < 32 && jw + lane < j_end) {
+    // (the lane index is taken afresh here: kept in a register across the products above it
+    // would be the one value too many and go through scratch memory)
+    int ln;
+    asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(ln));
+    if (rg == 0 && ln < 32 && jw + ln < j_end) {
       const float val = col * g.inv_group;
-      out[jw + lane] = val;
+      out[jw + ln] = val;
       vmin = fminf(vmin, val);
       vmax = fmaxf(vmax, val);
     }
@@ -593,7 +599,9 @@ __global__ __launch_bounds__(256, (F32 && D == 128) ? 1 : 2) void score_accum_ke
     vmin = fminf(vmin, __shfl_xor(vmin, o));
     vmax = fmaxf(vmax, __shfl_xor(vmax, o));
   }
-  if (lane == 0) range[((int64_t)hi * max_chunks + ch) * 4 + wave] = make_float2(vmin, vmax);
+  int ln0;
+  asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(ln0));
+  if (ln0 == 0) range[((int64_t)hi * max_chunks + ch) * 4 + wave] = make_float2(vmin, vmax);
 }
 
 // ---- pooling + forced positions (stand-alone scores) -------------------------------------
