@@ -7,6 +7,8 @@ A plain, slow, fp64 statement of what the path computes, written from the paper:
   allocate - Sec. 4.2 "Efficient Optimization via Convex Hull Relaxation", Eq. 9-10 and
              App. A.2: convex surrogate, non-increasing marginal gains, unit-by-unit
              greedy until B_total is spent (Eq. 8's equality constraint);
+  allocate_topk - the baseline allocation of Sec. 4.2's opening / Sec. 5.1 "Baselines": budgets
+             from a global top-k over the pooled surrogate scores of all heads;
   select   - Sec. 3.2 symbol table, M^pi(k): top-k by the metric, descending, with the
              fixed deterministic tie rule App. A.1 assumes (lowest index first);
   compact  - Sec. 3.2 / Eq. 3: the retained index set I_{l,h} as a dense per-head cache;
@@ -219,6 +221,39 @@ def allocate(curves: np.ndarray, knots: np.ndarray, b_min: np.ndarray, b_max: np
         budgets[h] += 1
         nxt[h] = next_gain(h)
     return budgets.astype(np.int32), 0
+
+
+def allocate_topk(scores: Sequence[np.ndarray], B_total: int, floor: int = 0) -> Tuple[np.ndarray, bool]:
+    """The baseline allocation Sec. 4.2's opening and Sec. 5.1 "Baselines" describe (global
+    top-k): the candidate positions of all heads are pooled and the B_total of largest surrogate
+    score are retained; a head's budget is the number of its positions among them.  `floor` is
+    the safeguard (App. D Table 8 gives AdaKV a safeguard ratio; the floor in tokens is the
+    caller's): the `floor` best positions of every head are retained first, the remaining
+    B_total - H * floor places go to the best of all other candidates.
+
+    scores: one float32 vector per head (lengths may differ).  Pooled candidates are ordered by
+    (score descending, head ascending, position ascending) - the tie rule of `select`, extended
+    by the head index (reading R-T1).  Returns (budgets int32 [H], feasible); infeasible
+    (floor beyond a head's length, B_total < H * floor, B_total beyond the number of candidates)
+    gives budgets = floor for every head.
+    """
+    H = len(scores)
+    lens = [int(len(s)) for s in scores]
+    budgets = np.full(H, floor, dtype=np.int32)
+    if floor < 0 or any(floor > n for n in lens) or B_total < H * floor or B_total > sum(lens):
+        return budgets, False
+    head, pos, val = [], [], []                    # every candidate outside the floors
+    for h, s in enumerate(scores):
+        outside = np.ones(lens[h], dtype=bool)
+        outside[select(np.asarray(s), floor)] = False
+        pos.append(np.nonzero(outside)[0])
+        head.append(np.full(len(pos[-1]), h, dtype=np.int64))
+        val.append(np.asarray(s, dtype=np.float64)[pos[-1]])
+    head, pos, val = np.concatenate(head), np.concatenate(pos), np.concatenate(val)
+    order = np.lexsort((pos, head, -val))          # last key is the primary one
+    taken = order[:B_total - H * floor]
+    budgets += np.bincount(head[taken], minlength=H).astype(np.int32)
+    return budgets, True
 
 
 def offsets_of(budgets: np.ndarray) -> np.ndarray:

@@ -13,10 +13,11 @@ import pytest
 from oracle import lukv_oracle as O
 from tests import test_oracle_allocate as TA
 from tests import test_oracle_score as TS
+from tests import test_oracle_topk_alloc as TK
 
 PUBLIC = ["window_attention_sum", "window_lse", "max_pool_1d", "score", "concave_hull", "marginal_gains",
           "_gain_of_unit", "_slope", "allocate", "select", "compact", "offsets_of", "profile_build",
-          "budgets_from_profile", "decode_attention", "utility_curve"]
+          "budgets_from_profile", "decode_attention", "utility_curve", "allocate_topk"]
 
 MUTANTS = {
     # name: (snippet, replacement, pin that must fail)
@@ -98,6 +99,21 @@ MUTANTS = {
     "topk_smallest": ('order = np.argsort(-s.astype(np.float64), kind="stable")',
                       'order = np.argsort(s.astype(np.float64), kind="stable")',
                       lambda: TA.test_select_brute_force_with_ties(0)),
+    "global_topk_takes_smallest": ("order = np.lexsort((pos, head, -val))", "order = np.lexsort((pos, head, val))",
+                                   lambda: TK.test_handworked_global_topk()),
+    "global_topk_ties_to_highest_head": ("order = np.lexsort((pos, head, -val))",
+                                         "order = np.lexsort((pos, -head, -val))",
+                                         lambda: TK.test_ties_go_to_the_lowest_head_then_the_lowest_position()),
+    "global_topk_floor_counted_twice": ("outside[select(np.asarray(s), floor)] = False", "pass",
+                                        lambda: TK.test_handworked_global_topk()),
+    "global_topk_floor_not_deducted": ("taken = order[:B_total - H * floor]", "taken = order[:B_total]",
+                                       lambda: TK.test_handworked_global_topk()),
+    "global_topk_floor_guards_worst_positions": ("outside[select(np.asarray(s), floor)] = False",
+                                                 "outside[select(-np.asarray(s), floor)] = False",
+                                                 lambda: TK.test_equals_exhaustive_search_on_tiny_inputs(0)),
+    "global_topk_accepts_too_large_B": ("or B_total < H * floor or B_total > sum(lens):",
+                                        "or B_total < H * floor:",
+                                        lambda: TK.test_infeasible_cases()),
 }
 
 
