@@ -115,6 +115,26 @@ int lukv_allocate(int32_t n_problems, int32_t n_heads, int32_t n_grid,
                   int32_t* budgets, int64_t* offsets, int32_t* status,
                   void* ws, int64_t ws_bytes, void* stream);
 
+/* Alternative to lukv_allocate: the baseline allocation Sec. 4.2's opening and Sec. 5.1
+ * "Baselines" describe (global top-k over surrogate scores).  Per sequence the positions of all
+ * n_heads = n_layers * n_kv_heads heads are pooled and the B_total[s] of largest pooled score are
+ * retained; budgets[s][h] is the number of positions of head h among them.  The pooled order is
+ * score descending, then head ascending, then position ascending - the selection's tie rule
+ * extended by the head index - so lukv_select_compact with these budgets retains exactly that
+ * set.  b_floor >= 0 is a safeguard: every head first keeps its b_floor best positions, and the
+ * other B_total - n_heads * b_floor places go to the best of all remaining candidates.
+ *   pooled  device float32 [n_layers][n_kv_heads][total_tokens] as lukv_score writes it
+ *           (+inf = always kept); NaN is not allowed
+ *   B_total HOST int64 [n_seqs]
+ *   budgets device int32 [n_seqs][n_heads]     offsets device int64 [n_seqs * n_heads + 1]
+ *   status  device int32 [n_seqs]: 0, or LUKV_ST_INFEASIBLE when b_floor > L, B_total <
+ *           n_heads * b_floor or B_total > n_heads * L (then budgets = b_floor)
+ *   ws: lukv_workspace_bytes(cfg, 0) bytes.  Limit: n_heads <= 4096.
+ * The paper compares against this allocation; it gives no kernel for it. */
+int lukv_allocate_topk(const lukv_config* cfg, const float* pooled, const int64_t* B_total,
+                       int32_t b_floor, int32_t* budgets, int64_t* offsets, int32_t* status,
+                       void* ws, int64_t ws_bytes, void* stream);
+
 /* Steps 3+4: per head hi keep the budgets[hi] positions of largest pooled score (ties: lowest
  * position), and gather their K and V rows.
  *   pooled   device float32 [n_layers][n_kv_heads][total_tokens] (no NaN)

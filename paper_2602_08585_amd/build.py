@@ -14,7 +14,7 @@ COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I", os.path.j
           "-I", CSRC, "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
           "-Wno-unused-command-line-argument"]
 # per-file extras: the allocation compares fp64 gains bit for bit with a CPU, so nothing is fused
-SOURCES = {"api.hip": [], "score.hip": [], "select.hip": [], "decode.hip": [], "profile.hip": [], "bench.hip": [],
+SOURCES = {"api.hip": [], "score.hip": [], "select.hip": [], "decode.hip": [], "profile.hip": [], "bench.hip": [], "topk_alloc.hip": [],
            "allocate.hip": ["-ffp-contract=off"]}
 
 

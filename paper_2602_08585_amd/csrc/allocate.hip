@@ -106,6 +106,10 @@ AllocIO make_alloc_io(int32_t n_problems, int32_t n_heads, int32_t n_grid, const
   return io;
 }
 
+void launch_offsets(const int32_t* budgets, int64_t* offsets, int64_t n_all, hipStream_t st) {
+  hipLaunchKernelGGL(offsets_kernel, dim3(1), dim3(256), 0, st, budgets, offsets, n_all);
+}
+
 void launch_allocate_vertices(const AllocIO& io, hipStream_t st) {
   const int bpp = alloc_blocks_a(io.n_heads, io.n_grid);
   hipLaunchKernelGGL(allocate_vertices_kernel, dim3(io.n_problems * bpp), dim3(256), 0, st, io, bpp);

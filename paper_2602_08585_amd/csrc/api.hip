@@ -157,6 +157,7 @@ WsLayout make_layout(const HostCfg& hc, int32_t n_grid, bool alloc_only) {
   w.keepmask = take(n_sel * 1024 * 4);
   w.runpre = take(n_sel * 1032 * 4);
   w.head_flag = take(n_sel * 4);
+  w.topk = take(alloc_only ? 0 : topk_workspace_bytes(hc.seq.n_seqs, hc.g.n_layers * hc.g.n_kv_heads));
   w.total = off;
   return w;
 }
@@ -244,6 +245,21 @@ int lukv_allocate(int32_t n_problems, int32_t n_heads, int32_t n_grid, const flo
   hipStream_t st = static_cast<hipStream_t>(stream);
   return launch_allocate(make_alloc_io(n_problems, n_heads, n_grid, curves, knots, b_min, b_max, B_total,
                                        budgets, offsets, status, lay, (char*)ws), st);
+}
+
+int lukv_allocate_topk(const lukv_config* cfg, const float* pooled, const int64_t* B_total, int32_t b_floor,
+                       int32_t* budgets, int64_t* offsets, int32_t* status, void* ws, int64_t ws_bytes,
+                       void* stream) {
+  HostCfg hc;
+  int rc = validate_config(cfg, &hc);
+  if (rc) return rc;
+  if (!pooled || !B_total || !budgets || !offsets || !status || b_floor < 0) return LUKV_EINVAL;
+  for (int i = 0; i < hc.seq.n_seqs; ++i)
+    if (B_total[i] < 0) return LUKV_EINFEASIBLE;
+  const WsLayout lay = make_layout(hc, 0, false);
+  if ((rc = check_ws(lay, ws, ws_bytes))) return rc;
+  return launch_allocate_topk(hc, pooled, B_total, b_floor, budgets, offsets, status, (char*)ws + lay.topk,
+                              static_cast<hipStream_t>(stream));
 }
 
 int lukv_select_compact(const lukv_config* cfg, const float* pooled, const int32_t* budgets,

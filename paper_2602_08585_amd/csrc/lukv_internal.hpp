@@ -62,6 +62,7 @@ struct WsLayout {
   int64_t keepmask;              // u32 [n_hi * 1024] whole-head selection: keep bits of every 32-position run
   int64_t runpre;                // u32 [n_hi * 1032] kept rows before every run (entry 1024: the head's total)
   int64_t head_flag;             // u32 [n_hi] status bits a head raised
+  int64_t topk;                  // scratch of the global top-k allocation
   int64_t total;
   int32_t n_hi, max_chunks, max_slices, range_stride, rows_padded;
 };
@@ -100,6 +101,12 @@ AllocIO make_alloc_io(int32_t n_problems, int32_t n_heads, int32_t n_grid, const
                       const WsLayout& lay, char* ws);
 int launch_allocate(const AllocIO& io, hipStream_t st);
 void launch_allocate_vertices(const AllocIO& io, hipStream_t st);   // first phase only
+void launch_offsets(const int32_t* budgets, int64_t* offsets, int64_t n_all, hipStream_t st);   // prefix sum
+// baseline allocation by a global top-k over pooled scores (topk_alloc.hip); ws points at its
+// own scratch of topk_workspace_bytes
+int64_t topk_workspace_bytes(int32_t n_seqs, int32_t n_heads);
+int launch_allocate_topk(const HostCfg& hc, const float* scores, const int64_t* B_total, int32_t floor,
+                         int32_t* budgets, int64_t* offsets, int32_t* status, char* ws, hipStream_t st);
 // static profile (Eq. 11): io0 describes the calibration queries as allocation problems whose
 // budgets / status arrays are scratch; rho is a host array
 int launch_profile_build(const AllocIO& io0, int32_t L, int32_t n_rho, const double* rho, float* phi,

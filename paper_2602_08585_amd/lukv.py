@@ -35,7 +35,7 @@ EXPORTS = ("lukv_workspace_bytes", "lukv_allocate_workspace_bytes", "lukv_score"
            "lukv_select_compact", "lukv_evict", "lukv_score_lse", "lukv_evict_lse",
            "lukv_profile_workspace_bytes", "lukv_profile_curves", "lukv_profile_build", "lukv_budgets_from_profile",
            "lukv_evict_budgets", "lukv_decode_workspace_bytes", "lukv_decode_attention",
-           "lukv_evict_static", "lukv_strerror")
+           "lukv_evict_static", "lukv_allocate_topk", "lukv_strerror")
 # include/lukv_bench.h: instrumentation for programs that time the path
 BENCH_EXPORTS = ("lukv_set_stage_events", "lukv_stage_name", "lukv_bench_stream_read", "lukv_bench_copy")
 LUKV_STATIC_SCRATCH_BYTES = 16 << 20
@@ -79,6 +79,7 @@ def load_library() -> ctypes.CDLL:
     lib.lukv_allocate_workspace_bytes.argtypes = [I32, I32, I32, ctypes.POINTER(I64)]
     lib.lukv_score.argtypes = [CP, P, P, P, P, I64, P]
     lib.lukv_allocate.argtypes = [I32, I32, I32, P, P, P, P, ctypes.POINTER(I64), P, P, P, P, I64, P]
+    lib.lukv_allocate_topk.argtypes = [CP, P, ctypes.POINTER(I64), I32, P, P, P, P, I64, P]
     lib.lukv_select_compact.argtypes = [CP, P, P, P, P, P, I64, P, P, P, P, P, I64, P]
     lib.lukv_evict.argtypes = [CP, P, P, P, I32, P, P, P, P, ctypes.POINTER(I64),
                                P, P, P, P, P, P, P, P, I64, P]
@@ -233,6 +234,14 @@ def lukv_allocate(n_problems: int, n_heads: int, n_grid: int, curves, knots, b_m
                                         _ptr(b_min), _ptr(b_max), Bp, _ptr(budgets), _ptr(offsets),
                                         _ptr(status), _ptr(ws), ws.numel(), _stream(stream)),
            "lukv_allocate")
+
+
+def lukv_allocate_topk(cfg: Config, pooled, B_total: Sequence[int], b_floor: int, budgets, offsets, status,
+                       ws, stream=None) -> None:
+    keep, Bp = _host_i64(B_total)
+    _check(load_library().lukv_allocate_topk(ctypes.byref(cfg.to_c()), _ptr(pooled), Bp, int(b_floor),
+                                             _ptr(budgets), _ptr(offsets), _ptr(status), _ptr(ws),
+                                             ws.numel(), _stream(stream)), "lukv_allocate_topk")
 
 
 def lukv_select_compact(cfg: Config, pooled, budgets, offsets, k, v, out_rows: int, kept_idx, k_out,

@@ -127,6 +127,21 @@ def test_host_refusals_of_the_profile_and_lse_entry_points():
                                   None, fake, fake, 1 << 40, None) == lukv.LUKV_EINVAL
 
 
+def test_host_refusals_of_the_topk_allocation():
+    lib = lukv.load_library()
+    fake = ctypes.c_void_p(256)       # never dereferenced
+    c = _cfg().to_c()
+    B = (ctypes.c_int64 * 1)(1000)
+    neg = (ctypes.c_int64 * 1)(-1)
+    args = lambda Bp, floor, ws_bytes: (ctypes.byref(c), fake, Bp, floor, fake, fake, fake, fake, ws_bytes, None)
+    assert lib.lukv_allocate_topk(*args(B, -1, 1 << 40)) == lukv.LUKV_EINVAL
+    assert lib.lukv_allocate_topk(*args(neg, 0, 1 << 40)) == lukv.LUKV_EINFEASIBLE
+    assert lib.lukv_allocate_topk(*args(B, 0, 16)) == lukv.LUKV_EWORKSPACE
+    assert lib.lukv_allocate_topk(ctypes.byref(c), None, B, 0, fake, fake, fake, fake, 1 << 40, None) == lukv.LUKV_EINVAL
+    many = _cfg(n_layers=600, n_q_heads=8, n_kv_heads=8, qstride_layer=8 * 32 * 128, qstride_head=32 * 128).to_c()
+    assert lib.lukv_allocate_topk(ctypes.byref(many), fake, B, 0, fake, fake, fake, fake, 1 << 50, None) == lukv.LUKV_EINVAL
+
+
 def test_sequences_longer_than_the_limit_are_refused():
     with pytest.raises(lukv.LukvError):
         lukv.lukv_workspace_bytes(_cfg(cu_seqlens=[0, (1 << 20) + 1], stride_head=((1 << 20) + 1) * 128,
