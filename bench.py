@@ -365,13 +365,29 @@ def main() -> int:
         torch.cuda.synchronize()
         dus = np.array([ev[i].elapsed_time(ev[i + 1]) * 1e3 for i in range(n_rep)])
         dec_bytes = 2 * row_bytes + Hq * d * esz + Hq * d * 4
+        # what a plain read of the same bytes takes, timed the same way (one launch over K and V of
+        # a cache laid side by side): the ceiling a problem of this size can reach at all
+        kv = [torch.cat([ko.view(-1), vo.view(-1)]) for ko, vo in caches]
+        sink2 = torch.zeros(4 * 4096, dtype=torch.int32, device="cuda")
+        for i in range(n_dec):
+            lukv.lukv_bench_stream_read(kv[i], 2 * row_bytes, sink2, 1024)
+        ev[0].record()
+        for i in range(n_rep):
+            lukv.lukv_bench_stream_read(kv[i % n_dec], 2 * row_bytes, sink2, 1024)
+            ev[i + 1].record()
+        torch.cuda.synchronize()
+        rus = float(np.median([ev[i].elapsed_time(ev[i + 1]) * 1e3 for i in range(n_rep)]))
+        del kv
         decode = {"what": "lukv_decode_attention: one decode query per head over the packed cache the step "
                           "leaves (K and V rows of all 8 heads, %d rows), 12 rotating caches" % rows,
                   "us_median": round(float(np.median(dus)), 2), "us_min": round(float(dus.min()), 2),
                   "alg_bytes": dec_bytes,
                   "GBs": round(dec_bytes / (float(np.median(dus)) * 1e-6) / 1e9, 1),
                   "frac_of_hbm_peak": round(dec_bytes / (float(np.median(dus)) * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
-                  "frac_of_read_ceiling": round(dec_bytes / (float(np.median(dus)) * 1e-6) / 1e9 / read_gbs, 4)}
+                  "frac_of_read_ceiling": round(dec_bytes / (float(np.median(dus)) * 1e-6) / 1e9 / read_gbs, 4),
+                  "plain_read_of_the_same_bytes_us": round(rus, 2),
+                  "frac_of_plain_read_of_the_same_bytes": round(rus / float(np.median(dus)), 4),
+                  "how": "median over 48 calls, an event after every call (two kernels per call)"}
         del caches
 
     # ---- CPU oracle on the same workload (one full layer = one step), this host -------------
