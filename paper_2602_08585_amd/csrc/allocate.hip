@@ -110,9 +110,8 @@ void launch_offsets(const int32_t* budgets, int64_t* offsets, int64_t n_all, hip
   hipLaunchKernelGGL(offsets_kernel, dim3(1), dim3(256), 0, st, budgets, offsets, n_all);
 }
 
-void launch_allocate_vertices(const AllocIO& io, hipStream_t st) {
-  const int bpp = alloc_blocks_a(io.n_heads, io.n_grid);
-  hipLaunchKernelGGL(allocate_vertices_kernel, dim3(io.n_problems * bpp), dim3(256), 0, st, io, bpp);
+void launch_allocate_budgets(const AllocIO& io, hipStream_t st) {
+  launch_staged(kStAllocate, allocate_budgets_kernel, dim3(io.n_problems), dim3(1024), st, io);
 }
 
 int launch_allocate(const AllocIO& io, hipStream_t st) {

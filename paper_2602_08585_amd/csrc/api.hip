@@ -210,7 +210,7 @@ static int score_impl(const lukv_config* cfg, const void* q_win, const void* k, 
   const WsLayout lay = make_layout(hc, 0, false);
   if ((rc = check_ws(lay, ws, ws_bytes))) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  if ((rc = launch_score_raw(hc, lay, q_win, k, lse, nullptr, false, (char*)ws, st))) return rc;
+  if ((rc = launch_score_raw(hc, lay, q_win, k, lse, nullptr, (char*)ws, st))) return rc;
   return launch_pool(hc, lay, pooled, (char*)ws, st);
 }
 
@@ -308,20 +308,20 @@ static int evict_impl(const lukv_config* cfg, const void* q_win, const void* k, 
   // the caller asks for them
   float* scores = pooled ? pooled : (select_whole_head(hc) ? nullptr : reinterpret_cast<float*>(w + lay.pooled));
   int32_t* sel_status = status + cfg->n_seqs;
-  // the allocation never looks at scores: its two phases ride along as a few extra workgroups
-  // of the two score kernels (where they do not displace resident scoring workgroups), so the
-  // budgets are there when the selection starts; selection pools the raw metric on the fly
+  // the allocation never looks at scores: its first phase rides along in the score kernels, its
+  // second with the selection or between the two; selection pools the raw metric on the fly
   const int n_heads = hc.g.n_layers * hc.g.n_kv_heads;
   const AllocIO aio = make_alloc_io(cfg->n_seqs, n_heads, n_grid, curves, knots, b_min, b_max, B_total,
                                     budgets, offsets, status, lay, w);
   // Where the budget phase runs: with the whole-head selection, inside the head workgroups when
-  // the call holds one small allocation problem, else as extra workgroups of the accumulation
-  // kernel; with the per-slice selection, as extra workgroups of its first kernel.
+  // the call holds one small allocation problem, else in a launch of its own ahead of them (one
+  // workgroup per problem); with the per-slice selection, as extra workgroups of its first kernel.
   const bool whole = select_whole_head(hc);
   const bool b_in_head = whole && cfg->n_seqs == 1 && alloc_small_ok(n_heads, n_grid);
-  const bool b_in_accum = whole && !b_in_head;
-  if ((rc = launch_score_raw(hc, lay, q_win, k, lse, &aio, b_in_accum, w, st))) return rc;
-  rc = launch_select_compact(hc, lay, b_in_accum ? nullptr : &aio, reinterpret_cast<const float*>(w + lay.raw), true,
+  const bool b_alone = whole && !b_in_head;
+  if ((rc = launch_score_raw(hc, lay, q_win, k, lse, &aio, w, st))) return rc;
+  if (b_alone) launch_allocate_budgets(aio, st);
+  rc = launch_select_compact(hc, lay, b_alone ? nullptr : &aio, reinterpret_cast<const float*>(w + lay.raw), true,
                              scores, budgets, offsets, true, k, v, kept_idx, k_out, v_out, out_rows, sel_status,
                              w, st);
   return rc;
@@ -455,7 +455,7 @@ int lukv_evict_budgets(const lukv_config* cfg, const void* q_win, const void* k,
   hipStream_t st = static_cast<hipStream_t>(stream);
   char* w = (char*)ws;
   float* scores = pooled ? pooled : (select_whole_head(hc) ? nullptr : reinterpret_cast<float*>(w + lay.pooled));
-  if ((rc = launch_score_raw(hc, lay, q_win, k, lse, nullptr, false, w, st))) return rc;
+  if ((rc = launch_score_raw(hc, lay, q_win, k, lse, nullptr, w, st))) return rc;
   rc = launch_select_compact(hc, lay, nullptr, reinterpret_cast<const float*>(w + lay.raw), true, scores, budgets,
                              const_cast<int64_t*>(offsets), false, k, v, kept_idx, k_out, v_out, out_rows,
                              status, w, st);

@@ -80,12 +80,11 @@ SeqTab tiles_for(const SeqTab& seq, int tile, int shrink);  // tiles over (L_s -
 
 // Launchers (enqueue only; return a LUKV_* code).
 struct AllocIO;
-// raw (unpooled) metric into the workspace; aio != NULL: the allocation's first phase rides
-// along in the score kernels, and its second phase too if b_in_accum (budgets and status are then
-// complete when the second kernel ends; otherwise the selection carries it)
+// raw (unpooled) metric into the workspace; aio != NULL: the allocation's first phase (hull
+// vertices) rides along in the score kernels
 // lse != NULL: the window rows' log-sum-exp is given, pass A is not launched
 int launch_score_raw(const HostCfg& hc, const WsLayout& lay, const void* q, const void* k,
-                     const float* lse, const AllocIO* aio, bool b_in_accum, char* ws, hipStream_t st);
+                     const float* lse, const AllocIO* aio, char* ws, hipStream_t st);
 int launch_pool(const HostCfg& hc, const WsLayout& lay, float* pooled_out, char* ws, hipStream_t st);
 // aio != NULL: the allocation's second phase rides along in the first selection kernel
 int launch_select_compact(const HostCfg& hc, const WsLayout& lay, const AllocIO* aio,
@@ -100,7 +99,7 @@ AllocIO make_alloc_io(int32_t n_problems, int32_t n_heads, int32_t n_grid, const
                       const int64_t* B_total, int32_t* budgets, int64_t* offsets, int32_t* status,
                       const WsLayout& lay, char* ws);
 int launch_allocate(const AllocIO& io, hipStream_t st);
-void launch_allocate_vertices(const AllocIO& io, hipStream_t st);   // first phase only
+void launch_allocate_budgets(const AllocIO& io, hipStream_t st);    // second phase only (no offsets)
 void launch_offsets(const int32_t* budgets, int64_t* offsets, int64_t n_all, hipStream_t st);   // prefix sum
 // baseline allocation by a global top-k over pooled scores (topk_alloc.hip); ws points at its
 // own scratch of topk_workspace_bytes

@@ -362,27 +362,17 @@ __global__ __launch_bounds__(256, (F32 && D == 128) ? 1 : 2) void score_accum_ke
                                                           int rows_padded) {
   using T = Tile<F32, D, RG>;
   constexpr int kBufRows = T::kKeys > 32 * NBM ? T::kKeys : 32 * NBM;   // K tile or one Q row group
-  // (at least 32 KiB: the buffer is also the scratch of the allocation's budget phase)
-  constexpr int kBufU4 = kBufRows * T::kLdsRowU4 > 2048 ? kBufRows * T::kLdsRowU4 : 2048;
+  constexpr int kBufU4 = kBufRows * T::kLdsRowU4;
   __shared__ u32x4 ktile[kBufU4];
   __shared__ __align__(16) float rowc_s[kMaxRows];
   __shared__ float2 pm[1024];
   __shared__ float colred[4][32];
 
   if ((int)blockIdx.x < n_alloc_blocks) {
-    // Extra workgroups, dispatched first (no use of scores).  alloc_bpp == 0: one per allocation
-    // problem, the budgets (the hull vertices are there since the previous kernel; the K-tile
-    // buffer is the scratch).  alloc_bpp > 0: the hull vertices, when there is no statistics
-    // kernel to carry them.
-    static_assert(sizeof(ktile) >= 32768, "the budget phase needs 32 KiB of LDS");
-    if (blockIdx.y == 0 && blockIdx.z == 0) {
-      if (alloc_bpp == 0) {
-        if ((int)blockIdx.x < aio.n_problems)
-          alloc_phase_b(aio, blockIdx.x, reinterpret_cast<char*>(ktile), (int)sizeof(ktile));
-      } else if ((int)blockIdx.x / alloc_bpp < aio.n_problems) {
-        alloc_phase_a(aio, blockIdx.x / alloc_bpp, blockIdx.x % alloc_bpp);
-      }
-    }
+    // Extra workgroups, dispatched first (no use of scores): the hull vertices, when there is no
+    // statistics kernel to carry them.
+    if (blockIdx.y == 0 && blockIdx.z == 0 && (int)blockIdx.x / alloc_bpp < aio.n_problems)
+      alloc_phase_a(aio, blockIdx.x / alloc_bpp, blockIdx.x % alloc_bpp);
     return;
   }
   int seq, ch;
@@ -626,7 +616,7 @@ __global__ __launch_bounds__(256) void pool_kernel(Geom g, SeqTab tab, const flo
 // ---- launchers ---------------------------------------------------------------------------
 template <bool F32, int D, int NBM, int RG>
 static int launch_raw_t(const HostCfg& hc, const WsLayout& lay, const void* q, const void* k,
-                        const float* lse, const AllocIO* aio, bool b_in_accum, char* ws, hipStream_t st) {
+                        const float* lse, const AllocIO* aio, char* ws, hipStream_t st) {
   const Geom& g = hc.g;
   float* lpart = reinterpret_cast<float*>(ws + lay.partial);
   float* raw = reinterpret_cast<float*>(ws + lay.raw);
@@ -635,18 +625,15 @@ static int launch_raw_t(const HostCfg& hc, const WsLayout& lay, const void* q, c
   const SeqTab tabB = tiles_for(hc.seq, g.chunk_keys, g.window);
   AllocIO io;
   memset(&io, 0, sizeof(io));
-  // The allocation never looks at scores, so it rides in the score kernels.  First phase (hull
-  // vertices): spread over the prologues of the statistics kernel's workgroups, one knot per
-  // wave, when there are enough of them; else a few extra workgroups at the front of its grid.
-  // Without a statistics kernel (log-sum-exp supplied) the accumulation kernel carries it the
-  // same way.  Second phase (budgets): where the caller says - extra workgroups at the front of
-  // the accumulation kernel (b_in_accum; the vertices then need a launch of their own if there
-  // is no statistics kernel), or with the selection.  Extra workgroups are padded to a multiple
-  // of 8 so that a chunk lands on the same XCD (and its L2) in both passes.
+  // The allocation never looks at scores, so its first phase (hull vertices) rides in the score
+  // kernels: spread over the prologues of the statistics kernel's workgroups, one knot per wave,
+  // when there are enough of them; else a few extra workgroups at the front of its grid.  Without
+  // a statistics kernel (log-sum-exp supplied) the accumulation kernel carries it the same way.
+  // Extra workgroups are padded to a multiple of 8 so that a chunk lands on the same XCD (and its
+  // L2) in both passes.
   const int64_t wgsA = (int64_t)tabA.tile0[tabA.n_seqs] * g.n_kv_heads * g.n_layers;
   const int64_t wgsB = (int64_t)tabB.tile0[tabB.n_seqs] * g.n_kv_heads * g.n_layers;
-  int frontA = 0, bppA = 1, spreadA = 0, frontB = 0, bppB = 0, spreadB = 0;
-  bool vertices_alone = false;
+  int frontA = 0, bppA = 1, spreadA = 0, frontB = 0, bppB = 1, spreadB = 0;
   if (aio) {
     io = *aio;
     const int64_t n_knots = (int64_t)aio->n_problems * aio->n_heads * aio->n_grid;
@@ -654,10 +641,6 @@ static int launch_raw_t(const HostCfg& hc, const WsLayout& lay, const void* q, c
     if (!lse) {
       spreadA = alloc_spread_knots(n_knots, wgsA);
       if (!spreadA) { bppA = bpp; frontA = (aio->n_problems * bpp + 7) / 8 * 8; }
-      if (b_in_accum) frontB = (aio->n_problems + 7) / 8 * 8;
-    } else if (b_in_accum) {
-      vertices_alone = true;
-      frontB = (aio->n_problems + 7) / 8 * 8;
     } else {
       spreadB = alloc_spread_knots(n_knots, wgsB);
       if (!spreadB) { bppB = bpp; frontB = (aio->n_problems * bpp + 7) / 8 * 8; }
@@ -668,8 +651,6 @@ static int launch_raw_t(const HostCfg& hc, const WsLayout& lay, const void* q, c
   if (!lse)
     launch_staged(kStStats, score_stats_kernel<F32, D, NBM, RG>, gridA, dim3(256), st, g, tabA, io, frontA, bppA,
                   spreadA, (const char*)q, (const char*)k, lpart, lay.rows_padded);
-  else if (vertices_alone)
-    launch_allocate_vertices(*aio, st);
   launch_staged(kStAccum, score_accum_kernel<F32, D, NBM, RG>, gridB, dim3(256), st, g, tabB, io,
                 frontB, bppB, spreadB, (const char*)q, (const char*)k, (const float*)lpart, lse, raw,
                 range, lay.max_chunks, lay.rows_padded);
@@ -678,22 +659,22 @@ static int launch_raw_t(const HostCfg& hc, const WsLayout& lay, const void* q, c
 
 template <bool F32, int D, int NBM>
 static int launch_raw_rg(const HostCfg& hc, const WsLayout& lay, const void* q, const void* k,
-                         const float* lse, const AllocIO* aio, bool b_in_accum, char* ws, hipStream_t st) {
+                         const float* lse, const AllocIO* aio, char* ws, hipStream_t st) {
   switch (hc.g.row_groups) {
-    case 1: return launch_raw_t<F32, D, NBM, 1>(hc, lay, q, k, lse, aio, b_in_accum, ws, st);
-    case 2: return launch_raw_t<F32, D, NBM, 2>(hc, lay, q, k, lse, aio, b_in_accum, ws, st);
-    case 4: return launch_raw_t<F32, D, NBM, 4>(hc, lay, q, k, lse, aio, b_in_accum, ws, st);
+    case 1: return launch_raw_t<F32, D, NBM, 1>(hc, lay, q, k, lse, aio, ws, st);
+    case 2: return launch_raw_t<F32, D, NBM, 2>(hc, lay, q, k, lse, aio, ws, st);
+    case 4: return launch_raw_t<F32, D, NBM, 4>(hc, lay, q, k, lse, aio, ws, st);
   }
   return LUKV_EINVAL;
 }
 
 int launch_score_raw(const HostCfg& hc, const WsLayout& lay, const void* q, const void* k,
-                     const float* lse, const AllocIO* aio, bool b_in_accum, char* ws, hipStream_t st) {
+                     const float* lse, const AllocIO* aio, char* ws, hipStream_t st) {
   const Geom& g = hc.g;
-  if (!g.f32 && g.head_dim == 128) return launch_raw_rg<false, 128, 4>(hc, lay, q, k, lse, aio, b_in_accum, ws, st);
-  if (!g.f32 && g.head_dim == 64) return launch_raw_rg<false, 64, 4>(hc, lay, q, k, lse, aio, b_in_accum, ws, st);
-  if (g.f32 && g.head_dim == 64) return launch_raw_rg<true, 64, 4>(hc, lay, q, k, lse, aio, b_in_accum, ws, st);
-  if (g.f32 && g.head_dim == 128) return launch_raw_rg<true, 128, 2>(hc, lay, q, k, lse, aio, b_in_accum, ws, st);
+  if (!g.f32 && g.head_dim == 128) return launch_raw_rg<false, 128, 4>(hc, lay, q, k, lse, aio, ws, st);
+  if (!g.f32 && g.head_dim == 64) return launch_raw_rg<false, 64, 4>(hc, lay, q, k, lse, aio, ws, st);
+  if (g.f32 && g.head_dim == 64) return launch_raw_rg<true, 64, 4>(hc, lay, q, k, lse, aio, ws, st);
+  if (g.f32 && g.head_dim == 128) return launch_raw_rg<true, 128, 2>(hc, lay, q, k, lse, aio, ws, st);
   return LUKV_EDTYPE;
 }
 
