@@ -281,6 +281,18 @@ def main() -> int:
     copy_us = ceiling(lambda src, blocks: lukv.lukv_bench_copy(src, dst, CEILING_BYTES, blocks))
     read_gbs = CEILING_BYTES / (read_us * 1e-6) / 1e9
     copy_gbs = 2 * CEILING_BYTES / (copy_us * 1e-6) / 1e9
+    # a plain copy of as many bytes as the gather moves (kept K and V rows read and written), timed
+    # the same way: what a kernel of that size can reach at all
+    emit_bytes = 2 * rows * d * 2
+    emit_copy_us = None
+    if emit_bytes % 16 == 0 and emit_bytes <= CEILING_BYTES:
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2 * 12)]
+        for i in range(12):
+            ev[2 * i].record()
+            lukv.lukv_bench_copy(kflat[i % len(kflat)], dst, emit_bytes, 2048)
+            ev[2 * i + 1].record()
+        torch.cuda.synchronize()
+        emit_copy_us = float(np.median([ev[2 * i].elapsed_time(ev[2 * i + 1]) * 1e3 for i in range(2, 12)]))
     del sink, dst
 
     # ---- algorithmic bytes ---------------------------------------------------------------------
@@ -306,6 +318,9 @@ def main() -> int:
                    for n in stages if n in alg}
     step_gbs = b_alg / (ms_per_step * 1e-3) / 1e9
     ceil = {"stream_read_GBs": round(read_gbs, 1), "copy_GBs": round(copy_gbs, 1), "bytes": CEILING_BYTES,
+            "stream_read_us": round(read_us, 2), "copy_us": round(copy_us, 2),
+            "copy_of_the_gathers_bytes_us": None if emit_copy_us is None else round(emit_copy_us, 2),
+            "gathers_bytes": emit_bytes,
             "how": "plain 16-byte grid-stride kernels of liblukv over 64 MiB of cold data, median of 10 "
                    "launches between events, best of 1024/2048/4096/8192 workgroups; measured in this run"}
     if args.config == "long_128k":

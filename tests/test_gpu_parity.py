@@ -59,10 +59,14 @@ def small(name):
         # a one-token observation window (rows = G, padded to one 32-row block)
         "bf16_w1": dict(n_q_heads=4, n_kv_heads=1, head_dim=128, seq_lens=[300], window=1, n_sink=2),
         # 64 heads in the call: the selection takes its whole-head form (one workgroup per head),
-        # the allocation's budget phase rides in the second score kernel
+        # the allocation's budget phase runs inside it (one sequence) or in a launch of its own
         "bf16_64heads": dict(n_q_heads=16, n_kv_heads=8, head_dim=64, seq_lens=[1500], window=16, n_layers=8),
         "bf16_64heads_ragged": dict(n_q_heads=8, n_kv_heads=8, head_dim=128, seq_lens=[700, 1029], window=32,
                                     n_layers=4, pool_kernel=5),
+        # the largest GQA group the decode consumer takes (two passes of eight queries), and a group
+        # that fills the second pass only in part
+        "bf16_g16_w16": dict(n_q_heads=16, n_kv_heads=1, head_dim=64, seq_lens=[1300], window=16),
+        "f32_g12_w16": dict(n_q_heads=24, n_kv_heads=2, head_dim=64, seq_lens=[800], window=16, dtype=synth.F32),
         # shortest legal context: one prefix token beyond window + sink
         "bf16_short": dict(n_q_heads=4, n_kv_heads=1, head_dim=128, seq_lens=[37], window=32, n_sink=4,
                            keep_ratio=1.0, n_grid=4),
@@ -76,7 +80,7 @@ def small(name):
 
 SMALL = ["bf16_g4_w32", "bf16_g5_w32", "bf16_g4_w64", "bf16_g7_w16_d64", "bf16_ragged", "f32_d128",
          "f32_d64_peaky", "bf16_short", "bf16_g8_w64_rows512", "bf16_mha_pool1_nosink", "bf16_pool31",
-         "f32_d128_rows256", "bf16_w1", "bf16_64heads", "bf16_64heads_ragged"]
+         "f32_d128_rows256", "bf16_w1", "bf16_64heads", "bf16_64heads_ragged", "bf16_g16_w16", "f32_g12_w16"]
 
 
 def _problem(name):
@@ -832,7 +836,8 @@ def test_strided_inputs_and_custom_scale():
 
 
 @pytest.mark.parametrize("name", ["tiny", "bf16_g4_w32", "bf16_ragged", "bf16_g7_w16_d64", "f32_d128",
-                                  "bf16_mha_pool1_nosink", "bf16_g8_w64_rows512"])
+                                  "bf16_mha_pool1_nosink", "bf16_g8_w64_rows512", "bf16_g16_w16", "f32_g12_w16",
+                                  "bf16_64heads_ragged"])
 def test_decode_attention_over_the_packed_cache(name):
     """Evict, then run one decode step's attention over the compacted cache (Eq. 3) and compare
     with the oracle's attention over the rows the kept indices name."""
