@@ -225,7 +225,7 @@ def main() -> int:
     # own duration, as a profiler reports it ------------------------------------------------------
     n_ev = lukv.LUKV_NUM_STAGE_EVENTS
     names = [lukv.lukv_stage_name(j) for j in range(lukv.LUKV_NUM_STAGES)]
-    used = [j for j, n in enumerate(names) if n not in ("allocate", "pool")]
+    used = [j for j, n in enumerate(names) if n != "pool"]
     n_timed = min(args.steps, 64)
     ev_sets = []
     for _ in range(n_timed):

@@ -257,7 +257,7 @@ int lukv_decode_attention(const lukv_config* cfg, const void* q_dec, const void*
  * (LUKV_STATIC_SCRATCH_BYTES of device memory per GPU the library runs on, held until the process
  * ends); the call allocates and frees nothing.  A configuration whose lukv_workspace_bytes exceeds
  * LUKV_STATIC_SCRATCH_BYTES is refused with LUKV_EWORKSPACE (the 8B-shaped layer at 32k context
- * needs 7.6 MiB).  Every call on a GPU uses that GPU's one array: calls that overlap in time on
+ * needs 7.4 MiB).  Every call on a GPU uses that GPU's one array: calls that overlap in time on
  * the same GPU (different streams or threads) race and must be serialised by the caller.  The
  * array needs no clearing between calls (every word is written before it is read in a call). */
 #define LUKV_STATIC_SCRATCH_BYTES (16 << 20)
