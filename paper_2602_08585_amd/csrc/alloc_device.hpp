@@ -9,18 +9,21 @@
 // find the gain g* at which the cumulated units (largest gain first) reach the remaining
 // budget, give every head all its units above g*, and hand the units at exactly g* out in
 // head order.
-//   phase A: hull vertices by their definition, sixteen threads per (head, knot): knot g is a
-//            vertex of the upper concave hull iff every chord from an earlier knot to g is
-//            strictly steeper than every chord from g to a later knot (end knots always
-//            are).  All chords are independent fp64 divisions: no serial chain, any number
-//            of workgroups.
-//   phase B: one workgroup per problem: a segment per vertex (to the next vertex), clipped to
-//            (b_min, min(b_max, last knot)], gain as an order-preserving 64-bit key; weighted
-//            radix select for g* (by the whole workgroup, digits of up to 11 bits over the
-//            bits in which the keys differ, for up to 1024 heads; a general form on one wave
-//            with 8-bit digits beyond that); budgets per head, ties by a prefix sum over
-//            heads.  The row offsets (prefix sum of all budgets) are written by whoever
-//            consumes the budgets next.
+//   phase A: hull vertices by the chord criterion: knot g is a vertex of the upper concave hull
+//            iff every chord from an earlier knot to g is strictly steeper than every chord
+//            from g to a later knot (end knots always are).  All chords are independent fp64
+//            divisions: no serial chain.  Two forms: one wave per (head, knot), for callers
+//            that spread the knots over the prologues of another kernel's workgroups, and
+//            sixteen threads per knot in workgroups of their own.
+//   phase B: budgets.  Small problems (up to 1024 knots and 64 heads): 1024 threads, one per
+//            knot; vertices are compacted into live segments, gains ranked in parallel, ties
+//            handed out in head order.  Otherwise one workgroup per problem: a segment per
+//            vertex (to the next vertex), clipped to (b_min, min(b_max, last knot)], gain as an
+//            order-preserving 64-bit key; weighted radix select for g* (by the whole
+//            workgroup, digits of up to 11 bits over the bits in which the keys differ, for
+//            up to 1024 heads; a general form on one wave with 8-bit digits beyond that);
+//            budgets per head, ties by a prefix sum over heads.  The row offsets (prefix sum
+//            of all budgets) are written by whoever consumes the budgets next.
 //
 // Nothing here may be fused: a gain is one fp64 subtract and one fp64 divide, so that it
 // compares bit for bit like the same expression evaluated on a CPU.

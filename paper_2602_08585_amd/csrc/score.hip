@@ -4,10 +4,14 @@
 //
 // Two streaming passes over K per (layer, sequence, KV head):
 //   stats  - S = K_tile * Q^T on the matrix cores; every lane owns one query row of a 32x32
-//            block and folds its 16 logits into a running (max, sum exp2) pair; a workgroup
-//            leaves one pair per row for its chunk of keys.
-//   accum  - merges the head's per-chunk pairs into one constant per row, c_r = max_r * a +
-//            log2(sum_r), a = scale * log2(e) (or takes the caller's log-sum-exp); then
+//            block and folds its 16 logits into a running (max, sum exp2) pair; per granule of
+//            keys the workgroup leaves one float per row, l = max * a + log2(sum),
+//            a = scale * log2(e).  A granule is 512 keys, doubled until the sequence has at most
+//            64 of them: it depends on the sequence length only, a workgroup's chunk is a whole
+//            number of granules, and the merge below runs over granules in index order - so a
+//            score does not depend on how a call is cut into workgroups.
+//   accum  - merges the head's granule values into one constant per row, c_r = M + log2(sum
+//            exp2(l - M)), M = max l (or takes the caller's log-sum-exp); then
 //            S = Q * K_tile^T, so that a lane owns one key column; P = exp2(S*a - c_r) is
 //            summed over the G*w rows in registers and written as the unpooled metric,
 //            together with the (min, max) of what each wave wrote.
@@ -24,8 +28,9 @@
 // "half hf = l/32 owns elements [hf*D/2, (hf+1)*D/2) of the row", so any internal ordering
 // of k is the same on both sides.  Output: acc[v] is row 8*(v/4) + 4*(l/32) + v%4, column l%32.
 //
-// When the fused path asks for it, the first blockIdx.x values of the two kernels run the two
-// phases of the budget allocation instead of scoring (it does not depend on scores).
+// When the fused path asks for it, the hull vertices of the budget allocation (which does not
+// depend on scores) are computed along the way: one knot per wave in the workgroups' prologues,
+// or, in calls with few workgroups, by a few extra workgroups at the front of the grid.
 #include <string.h>
 
 #include <type_traits>

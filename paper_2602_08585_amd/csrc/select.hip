@@ -19,6 +19,9 @@
 //               leaves, per slice, the kept rows and the ties before it.
 //   sel_emit  - one workgroup per slice: keep (key > T) plus the first r ties by position,
 //               write ascending positions and copy the K and V rows (16 bytes per lane).
+// Calls with many heads and sequences of at most 32768 tokens take the whole-head form instead
+// (sel_head, sel_gather, further below): one workgroup per head keeps the head's keys in
+// registers and leaves a keep mask, a gather kernel copies the rows.
 // No counter, flag or fence between workgroups anywhere: kernel boundaries order the phases.
 #include <string.h>
 
