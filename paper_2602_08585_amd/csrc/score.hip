@@ -233,7 +233,6 @@ __global__ __launch_bounds__(256, (F32 && D == 128) ? 1 : 2) void score_stats_ke
   // their way, so the divisions run while the tile is in flight.
   const int64_t a_item = spread_item(aio, alloc_spread, n_alloc_blocks);
   AllocKnotLoad a_ld;
-  if (a_item >= 0) a_ld = alloc_knot_load(aio, a_item);
   // byte offsets inside one head's keys fit 32 bits (checked on the host)
   const unsigned tok_bytes = (unsigned)(g.st * T::kEsize);
   const int ld_row0 = T::kPrivate ? 32 * (int)(threadIdx.x >> 6) + (int)(threadIdx.x & 63) / T::kRowU4
@@ -251,6 +250,9 @@ __global__ __launch_bounds__(256, (F32 && D == 128) ? 1 : 2) void score_stats_ke
     u32x4 qtmp[QStage<F32, D, NBM>::kLoads];
     q_fetch<F32, D, NBM, QStage<F32, D, NBM>::kLoads>(qtmp, g, q, layer, kvh, seq, 0);
     k_issue<F32, D, RG, T::kLoads>(pre, kbase, ld_off, ld_stride, ld_last);
+    // the allocation's knot of this wave: its loads are cold and go out last, so that nothing the
+    // workgroup needs first waits behind them; they are consumed once the first tile is in LDS
+    if (a_item >= 0) a_ld = alloc_knot_load(aio, a_item);
     for (int grp = 0; grp < RG; ++grp) {
       if (grp) q_fetch<F32, D, NBM, QStage<F32, D, NBM>::kLoads>(qtmp, g, q, layer, kvh, seq, grp);
       if (grp) __syncthreads();
@@ -259,8 +261,6 @@ __global__ __launch_bounds__(256, (F32 && D == 128) ? 1 : 2) void score_stats_ke
       if (rg == grp) q_pick<F32, D, NBM, T::kHalfU4>(qreg, ktile, lane);
     }
   }
-  // the allocation's knot of this wave: its loads are older than the queries', so they are back
-  if (a_item >= 0) alloc_knot_finish(aio, a_item, a_ld);
   __syncthreads();   // the buffer now turns into the K tile
 
   // window row index of this lane's query in every block (for the causal range)
@@ -302,12 +302,17 @@ __global__ __launch_bounds__(256, (F32 && D == 128) ? 1 : 2) void score_stats_ke
     __syncthreads();   // wstat is rewritten by the next granule
   };
 
-  for (int j0 = j_begin; j0 < j_end; j0 += T::kKeys) {
+  // One tile.  The first one is a copy of its own (first_tag), so that the knot's registers are
+  // not carried through the loop.
+  auto tile = [&](int j0, auto first_tag) {
     tile_sync<T::kPrivate>();      // the previous tile has been read
     k_commit<F32, D, RG, T::kLoads>(pre, ktile, ld_lds);
     tile_sync<T::kPrivate>();
     ld_off += ld_tile;
     if (j0 + T::kKeys < j_end) k_issue<F32, D, RG, T::kLoads>(pre, kbase, ld_off, ld_stride, ld_last);
+    if constexpr (decltype(first_tag)::value) {
+      if (a_item >= 0) alloc_knot_finish(aio, a_item, a_ld);
+    }
     const int jw = j0 + 32 * kt;   // first key of this wave's 32-key subtile
     if (jw < j_end) {              // wave-uniform
       u32x4 kreg[T::kHalfU4];
@@ -353,7 +358,10 @@ __global__ __launch_bounds__(256, (F32 && D == 128) ? 1 : 2) void score_stats_ke
     }
     const int j_next = j0 + T::kKeys;
     if (j_next >= j_end || j_next % gran == 0) publish((j_next - 1) / gran);   // uniform over the workgroup
-  }
+  };
+  if (j_begin < j_end) tile(j_begin, std::true_type{});
+  else if (a_item >= 0) alloc_knot_finish(aio, a_item, a_ld);
+  for (int j0 = j_begin + T::kKeys; j0 < j_end; j0 += T::kKeys) tile(j0, std::false_type{});
 }
 
 // ---- pass B: normalised window sums ------------------------------------------------------
